@@ -1,0 +1,184 @@
+/*
+ * innerq.h -- C ABI of libinnerq: decode attention over a KV cache quantised
+ * group-wise along the inner dimension (InnerQ, arXiv 2602.23200), for AMD
+ * MI355X (gfx950).
+ *
+ * Conventions that hold for every entry point
+ *   - Plain C: no C++ types, no exceptions.  Every call returns an
+ *     innerq_status_t (0 = OK, negative = error).  On error nothing has been
+ *     launched and no buffer has been touched.
+ *   - Every data pointer is DEVICE memory owned by the caller unless the
+ *     comment says "host".  The library never allocates, frees or keeps device
+ *     memory, never synchronises, and enqueues all its work on the HIP stream
+ *     the caller passes (a hipStream_t cast to void*; NULL = the null stream).
+ *   - Device pointers must be 16-byte aligned (the kernels use 128-bit loads).
+ *   - The library keeps no state between calls: the token counter lives in the
+ *     caller's innerq_cache_t (host memory) and is the same for the whole batch.
+ *   - Inputs are assumed finite; NaN/Inf in K, V or q give unspecified output.
+ *
+ * Notation (paper, Sections "KV Caching", "Quantization Scheme"):
+ *   B batch, Hq query heads, Hk kv heads (query head hq reads kv head
+ *   hq / (Hq/Hk)), d = head_dim, G = group size, b = bits, N = cached tokens.
+ *
+ * Partition of the N cached tokens of one tensor (Eq.
+ * kv_cache_init_quantized_window; Section "High-precision Window"):
+ *   sink      tokens [0, n_s)               fp16, n_s = min(N, w_sink)
+ *   quantised tokens [w_sink, w_sink + n_q) packed codes
+ *   recent    tokens [w_sink + n_q, N)      fp16 ring, slot = token index mod slots
+ *   with n_q = max(0, N - w_sink - w_recent), rounded DOWN to a multiple of G
+ *   for a tensor whose groups run along tokens (such a tensor can only quantise
+ *   G tokens at a time: Section "Latency", eviction pattern).
+ *
+ * Storage layout (this library's own; the paper does not define one)
+ *   "per-token" form (groups of G consecutive channels inside one token;
+ *   keys under inner grouping, values under outer grouping):
+ *     codes  u8   [B][Hk][capacity][d*b/8]   channel c at bit b*c of the row (little-endian)
+ *     scales fp16 [B][Hk][capacity][d/G]
+ *     zeros  fp16 [B][Hk][capacity][d/G]
+ *   "per-channel" form (groups of G consecutive tokens inside one channel;
+ *   values under inner grouping, keys under outer grouping):
+ *     codes  u8   [B][Hk][capacity/G][d][G*b/8]   token j of the group at bit b*j
+ *     scales fp16 [B][Hk][capacity/G][d]
+ *     zeros  fp16 [B][Hk][capacity/G][d]
+ *   fp16 form (kind INNERQ_KIND_FP16): codes fp16 [B][Hk][capacity][d], no scales/zeros.
+ *   Store row r holds token w_sink + r.
+ *   Stored b-bit field: the unsigned code of an asymmetric group (Eq. asym_quant),
+ *   code + 2^(b-1) for a symmetric group (signed code, Section "Asymmetric and
+ *   Symmetric Quantization").  The sign BIT of the stored scale is the mask M of
+ *   Section "Hybrid Quantization" (set = asymmetric); zeros holds Z for an
+ *   asymmetric group and +0 otherwise.  Decoding is Eq. hybrid_dequant:
+ *   x^ = |scale| * code + M * zero.
+ *   Windows: k_sink, v_sink fp16 [B][Hk][w_sink][d];
+ *   k_recent, v_recent fp16 [B][Hk][slots][d], slots = w_recent for a per-token
+ *   or fp16 tensor and w_recent + G for a per-channel tensor.
+ */
+#ifndef INNERQ_H
+#define INNERQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  INNERQ_OK = 0,
+  INNERQ_E_NULL = -1,        /* a required pointer is NULL */
+  INNERQ_E_ARG = -2,         /* inconsistent or out-of-range argument */
+  INNERQ_E_UNSUPPORTED = -3, /* valid in the paper, not built here (e.g. bits = 3) */
+  INNERQ_E_CAPACITY = -4,    /* the cache cannot hold that many tokens */
+  INNERQ_E_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
+  INNERQ_E_WORKSPACE = -6,   /* workspace smaller than innerq_workspace_bytes() */
+  INNERQ_E_HIP = -7          /* a kernel launch failed */
+} innerq_status_t;
+
+/* Quantisation mode of a tensor (Sections "Asymmetric and Symmetric
+ * Quantization", "Hybrid Quantization"). */
+typedef enum { INNERQ_SYM = 0, INNERQ_ASYM = 1, INNERQ_HYBRID = 2 } innerq_mode_t;
+
+/* Grouping of the cache.  INNER is the method (Section "InnerQ": keys per-token
+ * group-wise, values per-channel group-wise).  OUTER (keys per-channel, values
+ * per-token: the layout the paper compares against) and FP16 (no quantisation)
+ * exist so that the same calls drive the comparison kernels. */
+typedef enum { INNERQ_KIND_INNER = 0, INNERQ_KIND_OUTER = 1, INNERQ_KIND_FP16 = 2 } innerq_kind_t;
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim = 128; n_q_heads % n_kv_heads == 0 */
+  int32_t bits;            /* 2 or 4 */
+  int32_t group;           /* 32 or 64; head_dim % group == 0 */
+  int32_t w_sink;          /* >= 0 */
+  int32_t w_recent;        /* >= 1 */
+  int32_t k_mode, v_mode;  /* innerq_mode_t */
+  int32_t sym_denominator; /* symmetric scale = max|g| / den: 0 -> den = 2^(b-1)-1 (nothing
+                              saturates), 1 -> den = 2^b-1 (the formula as printed; codes saturate
+                              at -2^(b-1) and 2^(b-1)-1) */
+  int32_t kind;            /* innerq_kind_t */
+  int64_t capacity_tokens; /* most tokens the cache may ever hold; a multiple of group */
+} innerq_config_t;
+
+typedef struct {
+  void *k_codes, *k_scales, *k_zeros; /* device; zeros may be NULL when the mode is INNERQ_SYM; */
+  void *v_codes, *v_scales, *v_zeros; /* scales and zeros are NULL for INNERQ_KIND_FP16 */
+  void *k_sink, *v_sink;              /* device, may be NULL when w_sink == 0 */
+  void *k_recent, *v_recent;          /* device */
+  int64_t n_tokens;                   /* host: tokens cached so far; updated by innerq_quantize_append */
+} innerq_cache_t;
+
+typedef enum {
+  INNERQ_BUF_K_CODES = 0, INNERQ_BUF_K_SCALES, INNERQ_BUF_K_ZEROS,
+  INNERQ_BUF_V_CODES, INNERQ_BUF_V_SCALES, INNERQ_BUF_V_ZEROS,
+  INNERQ_BUF_K_SINK, INNERQ_BUF_V_SINK, INNERQ_BUF_K_RECENT, INNERQ_BUF_V_RECENT,
+  INNERQ_BUF_COUNT
+} innerq_buffer_t;
+
+/* Host-only helpers.  innerq_validate_config returns INNERQ_OK or the reason
+ * the configuration is rejected.  innerq_buffer_bytes gives the exact size of
+ * one cache buffer (0 for a buffer the configuration does not use, and for an
+ * invalid configuration).  innerq_workspace_bytes gives the size of the
+ * split-K scratch innerq_decode_attention needs (partial max, sum and output
+ * per query head and token split). */
+int innerq_validate_config(const innerq_config_t *cfg);
+size_t innerq_buffer_bytes(const innerq_config_t *cfg, int which /* innerq_buffer_t */);
+size_t innerq_workspace_bytes(const innerq_config_t *cfg);
+const char *innerq_status_string(int status);
+
+/* Counts of the partition above for tensor which = 0 (K) or 1 (V) when n_tokens
+ * are cached.  Host-only; out pointers are host memory and may be NULL. */
+int innerq_partition(const innerq_config_t *cfg, int which, int64_t n_tokens,
+                     int64_t *n_sink, int64_t *n_quantised, int64_t *n_recent);
+
+/* Per-channel key normalisation factors (Section "Per-channel Normalization of
+ * K"): norm_c = sqrt(max |K[.,.,.,c]|), computed once at the end of prefill.
+ *   k_fp16        device, fp16 [B][Hk][n_tokens][d], contiguous, read only
+ *   per_head      0: the maximum runs over batch, heads and tokens (the paper's
+ *                 definition; every row of the outputs is the same vector);
+ *                 1: over batch and tokens only, one vector per kv head
+ *   norm_out      device, fp32 [Hk][d]: what the caller multiplies into W_Q
+ *   inv_norm_out  device, fp32 [Hk][d]: 1/norm, what the caller multiplies into W_K
+ * A channel that is identically zero gets norm = 1.  n_tokens >= 1. */
+int innerq_calibrate_key_norm(const innerq_config_t *cfg, const void *k_fp16, int64_t n_tokens,
+                              int per_head, float *norm_out, float *inv_norm_out, void *hip_stream);
+
+/* Append t_new tokens to the cache (Eq. kv_cached; Section "High-precision
+ * Window"): the new k, v join the fp16 windows (first the sink window until it
+ * holds w_sink tokens, then the recent ring); recent tokens beyond the window
+ * are quantised (Eq. asym_quant / symmetric / hybrid rule of Figure "hybrid"),
+ * packed and moved to the quantised store -- one token per step for a
+ * per-token tensor, G tokens every G steps for a per-channel tensor.  The
+ * result does not depend on how the tokens were split over calls: appending
+ * the whole prefill at once equals Eq. kv_cache_init_quantized_window.
+ *   k_new, v_new  device, fp16 [B][Hk][t_new][d], contiguous, read only
+ *   k_inv_norm    device, fp32 [Hk][d] or NULL.  When given, every new key is
+ *                 replaced by fp16(float(k) * k_inv_norm[hk][c]) on its way in
+ *                 (for keys produced before the factors were folded into W_K).
+ * Quantiser arithmetic is IEEE fp32 on the fp16 inputs, scale rounded to fp16
+ * before the codes are formed, round-half-to-even.  On success
+ * cache->n_tokens += t_new.  INNERQ_E_CAPACITY if the result would exceed
+ * capacity_tokens. */
+int innerq_quantize_append(const innerq_config_t *cfg, innerq_cache_t *cache, const void *k_new,
+                           const void *v_new, int64_t t_new, const float *k_inv_norm,
+                           void *hip_stream);
+
+/* One decode step of attention for one new query per sequence (Eq. att:1-3
+ * with Eq. kv_cached_quantized): out = softmax(q K^T / sqrt(d)) V over all
+ * cache->n_tokens cached tokens, where K and V are the fp16 windows and the
+ * dequantised store (Eq. hybrid_dequant) -- dequantisation is fused into the
+ * two vector-matrix products, the quantised and window parts are merged before
+ * the softmax is normalised (Figure "quantization_overall").
+ *   q_fp16     device, fp16 [B][Hq][d], read only
+ *   q_scale    device, fp32 [Hk][d] or NULL.  When given, the query of head hq
+ *              is first replaced by fp16(float(q) * q_scale[hq/(Hq/Hk)][c])
+ *              (for callers that have not folded the key norm into W_Q).
+ *   out        device, [B][Hq][d], fp32 if out_is_fp32 else fp16
+ *   workspace  device scratch of at least innerq_workspace_bytes(cfg) bytes;
+ *              contents need not be initialised and are undefined afterwards
+ * Accumulation is fp32.  n_tokens must be >= 1. */
+int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *cache,
+                            const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INNERQ_H */

@@ -1,0 +1,193 @@
+"""ctypes binding of libinnerq.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; this module turns
+torch tensors into device pointers, keeps the caller-owned cache buffers alive
+and raises on any non-zero status.  There is no CPU fallback: if the library is
+not built, importing it here fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libinnerq.so")
+
+SYM, ASYM, HYBRID = 0, 1, 2
+KIND_INNER, KIND_OUTER, KIND_FP16 = 0, 1, 2
+(BUF_K_CODES, BUF_K_SCALES, BUF_K_ZEROS, BUF_V_CODES, BUF_V_SCALES, BUF_V_ZEROS,
+ BUF_K_SINK, BUF_V_SINK, BUF_K_RECENT, BUF_V_RECENT, BUF_COUNT) = range(11)
+BUFFER_NAMES = ("k_codes", "k_scales", "k_zeros", "v_codes", "v_scales", "v_zeros",
+                "k_sink", "v_sink", "k_recent", "v_recent")
+
+OK, E_NULL, E_ARG, E_UNSUPPORTED, E_CAPACITY, E_ALIGN, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4, -5, -6, -7
+
+
+class innerq_config_t(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("w_sink", C.c_int32), ("w_recent", C.c_int32), ("k_mode", C.c_int32),
+                ("v_mode", C.c_int32), ("sym_denominator", C.c_int32), ("kind", C.c_int32),
+                ("capacity_tokens", C.c_int64)]
+
+
+class innerq_cache_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES] + [("n_tokens", C.c_int64)]
+
+
+class InnerQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libinnerq.so (built by __graft_entry__.build / paper_2602_23200_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2602_23200_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        cfgp, cachep = C.POINTER(innerq_config_t), C.POINTER(innerq_cache_t)
+        L.innerq_validate_config.argtypes = [cfgp]
+        L.innerq_validate_config.restype = C.c_int
+        L.innerq_buffer_bytes.argtypes = [cfgp, C.c_int]
+        L.innerq_buffer_bytes.restype = C.c_size_t
+        L.innerq_workspace_bytes.argtypes = [cfgp]
+        L.innerq_workspace_bytes.restype = C.c_size_t
+        L.innerq_status_string.argtypes = [C.c_int]
+        L.innerq_status_string.restype = C.c_char_p
+        L.innerq_partition.argtypes = [cfgp, C.c_int, C.c_int64] + [C.POINTER(C.c_int64)] * 3
+        L.innerq_partition.restype = C.c_int
+        L.innerq_calibrate_key_norm.argtypes = [cfgp, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
+                                                C.c_void_p, C.c_void_p]
+        L.innerq_calibrate_key_norm.restype = C.c_int
+        L.innerq_quantize_append.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_void_p]
+        L.innerq_quantize_append.restype = C.c_int
+        L.innerq_decode_attention.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                              C.c_void_p, C.c_size_t, C.c_void_p]
+        L.innerq_decode_attention.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().innerq_status_string(status).decode()
+
+
+def make_config(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
+                k_mode=HYBRID, v_mode=HYBRID, sym_denominator=0, kind=KIND_INNER,
+                capacity_tokens=0) -> innerq_config_t:
+    return innerq_config_t(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
+                           k_mode, v_mode, sym_denominator, kind, capacity_tokens)
+
+
+def innerq_validate_config(cfg: innerq_config_t) -> int:
+    return lib().innerq_validate_config(C.byref(cfg))
+
+
+def innerq_buffer_bytes(cfg: innerq_config_t, which: int) -> int:
+    return lib().innerq_buffer_bytes(C.byref(cfg), which)
+
+
+def innerq_workspace_bytes(cfg: innerq_config_t) -> int:
+    return lib().innerq_workspace_bytes(C.byref(cfg))
+
+
+def innerq_partition(cfg: innerq_config_t, which: int, n_tokens: int):
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    st = lib().innerq_partition(C.byref(cfg), which, n_tokens, C.byref(a), C.byref(b), C.byref(c))
+    if st != OK:
+        raise InnerQError(st, "innerq_partition")
+    return a.value, b.value, c.value
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+@dataclass
+class Cache:
+    """Caller-owned cache buffers (torch uint8 tensors on the GPU) plus the C struct that points at them."""
+    cfg: innerq_config_t
+    buffers: dict
+    c: innerq_cache_t
+
+    @property
+    def n_tokens(self) -> int:
+        return self.c.n_tokens
+
+    def view(self, name: str, dtype, shape):
+        return self.buffers[name].view(dtype).view(*shape)
+
+
+def allocate_cache(cfg: innerq_config_t, device="cuda") -> Cache:
+    """Allocate every buffer the configuration needs, sized by innerq_buffer_bytes, zero-filled."""
+    import torch
+    st = innerq_validate_config(cfg)
+    if st != OK:
+        raise InnerQError(st, "allocate_cache")
+    bufs, c = {}, innerq_cache_t()
+    for i, name in enumerate(BUFFER_NAMES):
+        n = innerq_buffer_bytes(cfg, i)
+        bufs[name] = torch.zeros(n, dtype=torch.uint8, device=device) if n else None
+        setattr(c, name, _ptr(bufs[name]))
+    c.n_tokens = 0
+    return Cache(cfg, bufs, c)
+
+
+def allocate_workspace(cfg: innerq_config_t, device="cuda"):
+    import torch
+    return torch.empty(innerq_workspace_bytes(cfg), dtype=torch.uint8, device=device)
+
+
+def innerq_calibrate_key_norm(cfg: innerq_config_t, k, per_head: bool = False, stream=None):
+    """k: fp16 CUDA tensor [B, Hk, N, d] -> (norm, inv_norm) fp32 [Hk, d]."""
+    import torch
+    assert k.dtype == torch.float16 and k.is_contiguous() and k.is_cuda
+    norm = torch.empty(cfg.n_kv_heads, cfg.head_dim, dtype=torch.float32, device=k.device)
+    inv = torch.empty_like(norm)
+    st = lib().innerq_calibrate_key_norm(C.byref(cfg), k.data_ptr(), k.shape[2], int(per_head),
+                                         norm.data_ptr(), inv.data_ptr(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_calibrate_key_norm")
+    return norm, inv
+
+
+def innerq_quantize_append(cache: Cache, k_new, v_new, k_inv_norm=None, stream=None) -> None:
+    """k_new, v_new: fp16 CUDA tensors [B, Hk, T, d]."""
+    import torch
+    for t in (k_new, v_new):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert k_new.shape == v_new.shape
+    st = lib().innerq_quantize_append(C.byref(cache.cfg), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+                                      k_new.shape[2], _ptr(k_inv_norm), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_quantize_append")
+
+
+def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, stream=None):
+    """q: fp16 CUDA tensor [B, Hq, d] -> out [B, Hq, d] (fp32 unless an fp16 `out` is passed)."""
+    import torch
+    assert q.dtype == torch.float16 and q.is_contiguous() and q.is_cuda
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    assert out.is_contiguous() and out.dtype in (torch.float32, torch.float16)
+    st = lib().innerq_decode_attention(C.byref(cache.cfg), C.byref(cache.c), q.data_ptr(), _ptr(q_scale),
+                                       out.data_ptr(), int(out.dtype == torch.float32), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_decode_attention")
+    return out

@@ -1,0 +1,258 @@
+// C ABI of libinnerq (see include/innerq.h): argument checks, the window /
+// eviction arithmetic on the host, and kernel dispatch.  No device memory is
+// allocated here and nothing synchronises.
+#include "innerq_dev.h"
+
+using namespace innerq;
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline long long ceil_div(long long a, long long b) { return (a + b - 1) / b; }
+
+// Most token splits a launch may use for the quantised range; bounds the workspace.
+inline int split_cap(const innerq_config_t& c) {
+  long long s = ceil_div(4096, (long long)c.batch * c.n_kv_heads);
+  if (s < 4) s = 4;
+  if (s > 512) s = 512;
+  return (int)s;
+}
+inline int window_chunk_cap(const innerq_config_t& c) {
+  return (int)ceil_div((long long)c.w_sink + c.w_recent + 2LL * c.group, kWindowChunk) + 1;
+}
+
+int check_config(const innerq_config_t* c) {
+  if (!c) return INNERQ_E_NULL;
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return INNERQ_E_ARG;
+  if (c->n_q_heads % c->n_kv_heads != 0) return INNERQ_E_ARG;
+  if ((long long)c->batch * c->n_kv_heads > 65535) return INNERQ_E_ARG;
+  if (c->kind < INNERQ_KIND_INNER || c->kind > INNERQ_KIND_FP16) return INNERQ_E_ARG;
+  if (c->k_mode < INNERQ_SYM || c->k_mode > INNERQ_HYBRID) return INNERQ_E_ARG;
+  if (c->v_mode < INNERQ_SYM || c->v_mode > INNERQ_HYBRID) return INNERQ_E_ARG;
+  if (c->sym_denominator != 0 && c->sym_denominator != 1) return INNERQ_E_ARG;
+  if (c->w_sink < 0 || c->w_recent < 1) return INNERQ_E_ARG;
+  if (c->bits < 1 || c->bits > 8 || c->group < 1) return INNERQ_E_ARG;
+  if (c->head_dim % c->group != 0) return INNERQ_E_ARG;          // groups must tile the head dimension
+  if (c->capacity_tokens < 1 || c->capacity_tokens % c->group != 0) return INNERQ_E_ARG;
+  if (c->head_dim != kHeadDim) return INNERQ_E_UNSUPPORTED;
+  if (c->bits != 2 && c->bits != 4) return INNERQ_E_UNSUPPORTED;  // 3-bit presets of the paper: not built
+  if (c->group != 32 && c->group != 64) return INNERQ_E_UNSUPPORTED;
+  return INNERQ_OK;
+}
+
+bool uses_zeros(const innerq_config_t& c, int which) {
+  if (c.kind == INNERQ_KIND_FP16) return false;
+  return (which == 0 ? c.k_mode : c.v_mode) != INNERQ_SYM;
+}
+
+int check_cache(const innerq_config_t& c, const innerq_cache_t* k) {
+  if (!k) return INNERQ_E_NULL;
+  if (!k->k_codes || !k->v_codes || !k->k_recent || !k->v_recent) return INNERQ_E_NULL;
+  if (c.w_sink > 0 && (!k->k_sink || !k->v_sink)) return INNERQ_E_NULL;
+  if (c.kind != INNERQ_KIND_FP16) {
+    if (!k->k_scales || !k->v_scales) return INNERQ_E_NULL;
+    if (uses_zeros(c, 0) && !k->k_zeros) return INNERQ_E_NULL;
+    if (uses_zeros(c, 1) && !k->v_zeros) return INNERQ_E_NULL;
+  }
+  const void* ptrs[] = {k->k_codes, k->k_scales, k->k_zeros, k->v_codes, k->v_scales,
+                        k->v_zeros, k->k_sink,   k->v_sink,  k->k_recent, k->v_recent};
+  for (const void* p : ptrs)
+    if (p && misaligned(p)) return INNERQ_E_ALIGN;
+  if (k->n_tokens < 0 || k->n_tokens > c.capacity_tokens) return INNERQ_E_ARG;
+  return INNERQ_OK;
+}
+
+TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which, long long n) {
+  const Partition p = partition_of(c, which, n);
+  TensorView v;
+  v.codes = static_cast<const uint8_t*>(which == 0 ? k.k_codes : k.v_codes);
+  v.scales = static_cast<const __half*>(which == 0 ? k.k_scales : k.v_scales);
+  v.zeros = uses_zeros(c, which) ? static_cast<const __half*>(which == 0 ? k.k_zeros : k.v_zeros) : nullptr;
+  v.sink = static_cast<const __half*>(which == 0 ? k.k_sink : k.v_sink);
+  v.ring = static_cast<const __half*>(which == 0 ? k.k_recent : k.v_recent);
+  v.form = form_of(c.kind, which);
+  v.slots = ring_slots(c, which);
+  v.n_sink = (int)p.n_sink;
+  v.n_quant = p.n_quant;
+  return v;
+}
+
+}  // namespace
+
+extern "C" {
+
+int innerq_validate_config(const innerq_config_t* cfg) { return check_config(cfg); }
+
+const char* innerq_status_string(int status) {
+  switch (status) {
+    case INNERQ_OK: return "ok";
+    case INNERQ_E_NULL: return "a required pointer is NULL";
+    case INNERQ_E_ARG: return "inconsistent or out-of-range argument";
+    case INNERQ_E_UNSUPPORTED: return "configuration not supported by this build";
+    case INNERQ_E_CAPACITY: return "cache capacity exceeded";
+    case INNERQ_E_ALIGN: return "device pointer not 16-byte aligned";
+    case INNERQ_E_WORKSPACE: return "workspace too small";
+    case INNERQ_E_HIP: return "HIP kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t innerq_buffer_bytes(const innerq_config_t* cfg, int which) {
+  if (check_config(cfg) != INNERQ_OK || which < 0 || which >= INNERQ_BUF_COUNT) return 0;
+  const innerq_config_t& c = *cfg;
+  const size_t BH = (size_t)c.batch * c.n_kv_heads, d = (size_t)c.head_dim, cap = (size_t)c.capacity_tokens;
+  const int t = (which == INNERQ_BUF_K_CODES || which == INNERQ_BUF_K_SCALES || which == INNERQ_BUF_K_ZEROS ||
+                 which == INNERQ_BUF_K_SINK || which == INNERQ_BUF_K_RECENT) ? 0 : 1;
+  const int form = form_of(c.kind, t);
+  switch (which) {
+    case INNERQ_BUF_K_CODES: case INNERQ_BUF_V_CODES:
+      return form == kFp16 ? BH * cap * d * 2 : BH * cap * d * (size_t)c.bits / 8;
+    case INNERQ_BUF_K_SCALES: case INNERQ_BUF_V_SCALES:
+      return form == kFp16 ? 0 : BH * cap * d / (size_t)c.group * 2;
+    case INNERQ_BUF_K_ZEROS: case INNERQ_BUF_V_ZEROS:
+      return uses_zeros(c, t) ? BH * cap * d / (size_t)c.group * 2 : 0;
+    case INNERQ_BUF_K_SINK: case INNERQ_BUF_V_SINK:
+      return BH * (size_t)c.w_sink * d * 2;
+    default:
+      return BH * (size_t)ring_slots(c, t) * d * 2;
+  }
+}
+
+size_t innerq_workspace_bytes(const innerq_config_t* cfg) {
+  if (check_config(cfg) != INNERQ_OK) return 0;
+  const size_t heads = (size_t)cfg->batch * cfg->n_q_heads;
+  const size_t partials = (size_t)split_cap(*cfg) + window_chunk_cap(*cfg);
+  return heads * partials * (kHeadDim + 2) * sizeof(float) + 64;
+}
+
+int innerq_partition(const innerq_config_t* cfg, int which, int64_t n_tokens, int64_t* n_sink,
+                     int64_t* n_quantised, int64_t* n_recent) {
+  const int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  if ((which != 0 && which != 1) || n_tokens < 0) return INNERQ_E_ARG;
+  const Partition p = partition_of(*cfg, which, n_tokens);
+  if (n_sink) *n_sink = p.n_sink;
+  if (n_quantised) *n_quantised = p.n_quant;
+  if (n_recent) *n_recent = p.n_recent;
+  return INNERQ_OK;
+}
+
+int innerq_calibrate_key_norm(const innerq_config_t* cfg, const void* k_fp16, int64_t n_tokens, int per_head,
+                              float* norm_out, float* inv_norm_out, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  if (!k_fp16 || !norm_out || !inv_norm_out) return INNERQ_E_NULL;
+  if (n_tokens < 1 || (per_head != 0 && per_head != 1)) return INNERQ_E_ARG;
+  if (misaligned(k_fp16) || misaligned(norm_out) || misaligned(inv_norm_out)) return INNERQ_E_ALIGN;
+  const hipError_t e = launch_calibrate(static_cast<const __half*>(k_fp16), cfg->batch, cfg->n_kv_heads, n_tokens,
+                                        per_head, norm_out, inv_norm_out, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
+}
+
+int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new,
+                           const void* v_new, int64_t t_new, const float* k_inv_norm, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (t_new < 0) return INNERQ_E_ARG;
+  if (t_new == 0) return INNERQ_OK;
+  if (!k_new || !v_new) return INNERQ_E_NULL;
+  if (misaligned(k_new) || misaligned(v_new) || (k_inv_norm && misaligned(k_inv_norm))) return INNERQ_E_ALIGN;
+  const long long n0 = cache->n_tokens, n1 = n0 + t_new;
+  if (n1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+
+  QuantArgs a;
+  a.inv_norm = k_inv_norm;
+  a.batch = cfg->batch; a.n_kv_heads = cfg->n_kv_heads; a.bits = cfg->bits; a.group = cfg->group;
+  a.w_sink = cfg->w_sink; a.sym_den_literal = cfg->sym_denominator;
+  a.capacity = cfg->capacity_tokens; a.n_old = n0; a.t_new = t_new;
+  for (int w = 0; w < 2; ++w) {
+    QuantTensorJob& j = a.job[w];
+    j.codes = static_cast<uint8_t*>(w == 0 ? cache->k_codes : cache->v_codes);
+    j.scales = static_cast<__half*>(w == 0 ? cache->k_scales : cache->v_scales);
+    j.zeros = uses_zeros(*cfg, w) ? static_cast<__half*>(w == 0 ? cache->k_zeros : cache->v_zeros) : nullptr;
+    j.sink = static_cast<__half*>(w == 0 ? cache->k_sink : cache->v_sink);
+    j.ring = static_cast<__half*>(w == 0 ? cache->k_recent : cache->v_recent);
+    j.x_new = static_cast<const __half*>(w == 0 ? k_new : v_new);
+    j.form = form_of(cfg->kind, w);
+    j.mode = w == 0 ? cfg->k_mode : cfg->v_mode;
+    j.slots = ring_slots(*cfg, w);
+    // rows that leave the recent window during this call (oldest first)
+    j.row_begin = partition_of(*cfg, w, n0).n_quant;
+    j.row_end = partition_of(*cfg, w, n1).n_quant;
+    j.ring_from = cfg->w_sink + j.row_end;
+    j.normalise = (w == 0 && k_inv_norm) ? 1 : 0;
+  }
+  const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return INNERQ_E_HIP;
+  cache->n_tokens = n1;
+  return INNERQ_OK;
+}
+
+int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* q_fp16,
+                            const float* q_scale, void* out, int out_is_fp32, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (!q_fp16 || !out || !workspace) return INNERQ_E_NULL;
+  if (misaligned(q_fp16) || misaligned(out) || misaligned(workspace) || (q_scale && misaligned(q_scale)))
+    return INNERQ_E_ALIGN;
+  if (cache->n_tokens < 1) return INNERQ_E_ARG;
+  if (workspace_bytes < innerq_workspace_bytes(cfg)) return INNERQ_E_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const innerq_config_t& c = *cfg;
+  const long long N = cache->n_tokens;
+
+  AttnArgs a;
+  a.k = view_of(c, *cache, 0, N);
+  a.v = view_of(c, *cache, 1, N);
+  a.q = static_cast<const __half*>(q_fp16);
+  a.q_scale = q_scale;
+  a.out = out; a.out_is_fp32 = out_is_fp32;
+  a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
+  a.bits = c.bits; a.group = c.group; a.w_sink = c.w_sink;
+  a.capacity = c.capacity_tokens; a.n_tokens = N;
+
+  // Tokens [w_sink, w_sink + n_both) are in the quantised store for both K and V: the split-K
+  // range.  Everything else (sink window, recent windows, and the < G tokens quantised in only
+  // one of the two tensors) goes through the generic window pass.
+  const long long n_both = a.k.n_quant < a.v.n_quant ? a.k.n_quant : a.v.n_quant;
+  const long long n_sink = a.k.n_sink;
+  const long long win_b0 = c.w_sink + n_both, win_b1 = N > win_b0 ? N : win_b0;
+  const long long win_tokens = n_sink + (win_b1 - win_b0);
+  const int r = c.n_q_heads / c.n_kv_heads;
+  int n_splits = 0;
+  if (n_both > 0) {
+    const long long blocks_per_split = (long long)c.batch * c.n_kv_heads * ceil_div(r, kHeadTile);
+    long long s = ceil_div(2048, blocks_per_split);
+    const long long by_len = ceil_div(n_both, 128);
+    if (s > by_len) s = by_len;
+    if (s > split_cap(c)) s = split_cap(c);
+    if (s < 1) s = 1;
+    n_splits = (int)s;
+  }
+  const int n_win = (int)ceil_div(win_tokens, kWindowChunk);
+  if (n_win > window_chunk_cap(c)) return INNERQ_E_ARG;
+  a.n_partials = n_splits + n_win;
+  const size_t heads = (size_t)c.batch * c.n_q_heads;
+  a.ws_ml = static_cast<float*>(workspace);
+  a.ws_o = a.ws_ml + ((heads * a.n_partials * 2 + 3) / 4) * 4;
+
+  hipError_t e = hipSuccess;
+  if (n_splits > 0) {
+    e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+    if (e != hipSuccess) return INNERQ_E_HIP;
+  }
+  if (n_win > 0) {
+    e = launch_attention_generic(a, 0, n_sink, win_b0, win_b1, n_win, n_splits, stream);
+    if (e != hipSuccess) return INNERQ_E_HIP;
+  }
+  e = launch_attention_merge(a, stream);
+  return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Internal declarations shared by the HIP translation units of libinnerq.
+// Nothing here is part of the C ABI (see include/innerq.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/innerq.h"
+
+namespace innerq {
+
+constexpr int kHeadDim = 128;          // the only head_dim built
+constexpr int kWindowChunk = 256;      // tokens per work-group of the generic (window) kernel
+constexpr int kHeadTile = 4;           // query heads served by one work-group pass
+
+enum Form : int { kPerToken = 0, kPerChannel = 1, kFp16 = 2 };
+
+inline __host__ __device__ int form_of(int kind, int which) {
+  if (kind == INNERQ_KIND_FP16) return kFp16;
+  const int inner = which == 0 ? kPerToken : kPerChannel;
+  const int outer = which == 0 ? kPerChannel : kPerToken;
+  return kind == INNERQ_KIND_INNER ? inner : outer;
+}
+
+// One tensor (K or V) of the cache as the kernels see it.
+struct TensorView {
+  const uint8_t* codes;
+  const __half* scales;
+  const __half* zeros;
+  const __half* sink;
+  const __half* ring;
+  int form;            // Form
+  int slots;           // ring slots
+  int n_sink;          // tokens currently in the sink window
+  long long n_quant;   // tokens currently in the quantised store
+};
+
+struct Partition { long long n_sink, n_quant, n_recent; };
+
+inline Partition partition_of(const innerq_config_t& c, int which, long long n) {
+  Partition p;
+  p.n_sink = n < c.w_sink ? n : c.w_sink;
+  long long mid = n - c.w_sink - c.w_recent;
+  if (mid < 0) mid = 0;
+  if (form_of(c.kind, which) == kPerChannel) mid -= mid % c.group;
+  p.n_quant = mid;
+  p.n_recent = n - p.n_sink - mid;
+  return p;
+}
+
+inline int ring_slots(const innerq_config_t& c, int which) {
+  return c.w_recent + (form_of(c.kind, which) == kPerChannel ? c.group : 0);
+}
+
+// ---- launchers implemented in the kernel translation units --------------------------------
+
+struct QuantTensorJob {
+  // destination store
+  uint8_t* codes; __half* scales; __half* zeros; __half* sink; __half* ring;
+  const __half* x_new;       // [B][Hk][t_new][d]
+  int form, mode, slots;
+  long long row_begin, row_end;   // store rows to quantise in this call (token = w_sink + row)
+  long long ring_from;            // new tokens with index >= ring_from go to the ring
+  int normalise;                  // apply k_inv_norm to tokens taken from x_new
+};
+
+struct QuantArgs {
+  QuantTensorJob job[2];          // K, V
+  const float* inv_norm;          // [Hk][d] or null
+  int batch, n_kv_heads, bits, group, w_sink, sym_den_literal;
+  long long capacity, n_old, t_new;
+};
+
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream);
+hipError_t launch_calibrate(const __half* k, int batch, int n_kv_heads, long long n_tokens, int per_head,
+                            float* norm_out, float* inv_out, hipStream_t stream);
+
+struct AttnArgs {
+  TensorView k, v;
+  const __half* q;          // [B][Hq][d]
+  const float* q_scale;     // [Hk][d] or null
+  void* out; int out_is_fp32;
+  float* ws_ml;             // [B*Hq][n_partials][2]
+  float* ws_o;              // [B*Hq][n_partials][d]
+  int n_partials;           // partial slots per head in this launch
+  int batch, n_q_heads, n_kv_heads, bits, group, w_sink;
+  long long capacity, n_tokens;
+};
+
+// Generic (any form, element-by-element) partial attention over the token set
+// [a0,a1) U [b0,b1), cut into n_chunks equal chunks, written to partial slots
+// first_slot .. first_slot+n_chunks.
+hipError_t launch_attention_generic(const AttnArgs& a, long long a0, long long a1, long long b0, long long b1,
+                                    int n_chunks, int first_slot, hipStream_t stream);
+hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace innerq

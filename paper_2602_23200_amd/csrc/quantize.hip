@@ -1,0 +1,288 @@
+// Quantise / pack kernels, window copies and key-norm calibration.
+//
+// This translation unit is compiled with -ffp-contract=off: the integer codes
+// and the symmetric/asymmetric flag depend on every fp32 rounding, so each
+// multiply, add, subtract and divide below is a separate IEEE operation
+// (Section "Quantization Scheme", Eq. asym_quant; Figure "hybrid").
+#include "innerq_dev.h"
+
+namespace innerq {
+namespace {
+
+__device__ inline float h2f(__half h) { return __half2float(h); }
+
+// One quantisation group of G values.
+//   asymmetric (Eq. asym_quant):  Z = min, S = (max - Z) / (2^b - 1), code = clip(rint((x - Z) / S), 0, 2^b-1)
+//   symmetric:                    S = max|x| / den, code = clip(rint(x / S), -2^(b-1), 2^(b-1)-1)
+//   hybrid (Figure "hybrid"):     both; L1 reconstruction errors summed in index order; asymmetric
+//                                 only if its error is strictly smaller
+// The scale is rounded to fp16 (its stored precision) before the codes are formed.
+// Stored field: code (asymmetric) or code + 2^(b-1) (symmetric); scale sign bit = asymmetric.
+template <int G, int BITS>
+__device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den_literal,
+                                      uint32_t (&words)[G * BITS / 32], __half& scale, __half& zero) {
+  constexpr int W = G * BITS / 32;
+  constexpr int QMAX = (1 << BITS) - 1;
+  constexpr int HALF = 1 << (BITS - 1);
+  float mn = x[0], mx = x[0], am = fabsf(x[0]);
+#pragma unroll
+  for (int i = 1; i < G; ++i) {
+    mn = fminf(mn, x[i]);
+    mx = fmaxf(mx, x[i]);
+    am = fmaxf(am, fabsf(x[i]));
+  }
+  const float den = sym_den_literal ? (float)QMAX : (float)(HALF - 1);
+  const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
+  const __half Ss = __float2half_rn(am / den);
+  const float Saf = h2f(Sa), Ssf = h2f(Ss);
+  uint32_t wa[W], ws[W];
+#pragma unroll
+  for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
+  float ea = 0.f, es = 0.f;
+#pragma unroll
+  for (int i = 0; i < G; ++i) {
+    float ca = fminf(fmaxf(rintf((x[i] - mn) / Saf), 0.f), (float)QMAX);
+    ca = (Saf == 0.f) ? 0.f : ca;
+    float cs = fminf(fmaxf(rintf(x[i] / Ssf), (float)(-HALF)), (float)(HALF - 1));
+    cs = (Ssf == 0.f) ? 0.f : cs;
+    const float ra = Saf * ca + mn;
+    const float rs = Ssf * cs;
+    ea = ea + fabsf(x[i] - ra);
+    es = es + fabsf(x[i] - rs);
+    wa[(i * BITS) / 32] |= (uint32_t)(int)ca << ((i * BITS) % 32);
+    ws[(i * BITS) / 32] |= (uint32_t)((int)cs + HALF) << ((i * BITS) % 32);
+  }
+  const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
+#pragma unroll
+  for (int i = 0; i < W; ++i) words[i] = asym ? wa[i] : ws[i];
+  scale = asym ? __hneg(Sa) : Ss;
+  zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
+}
+
+// Where the fp16 row of token t (absolute index) of sequence-head bh lives when the quantiser
+// wants it: still in the recent ring if it was appended by an earlier call, else in x_new.
+__device__ inline const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
+                                          long long t, bool& from_new) {
+  from_new = t >= a.n_old;
+  if (from_new) return j.x_new + ((bh * a.t_new) + (t - a.n_old)) * kHeadDim;
+  return j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
+}
+
+template <int G, int BITS>
+__global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a) {
+  const QuantTensorJob& j = a.job[blockIdx.y];
+  const long long n_rows = j.row_end - j.row_begin;
+  if (n_rows <= 0) return;
+  const long long BH = (long long)a.batch * a.n_kv_heads;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  constexpr int W = G * BITS / 32;
+
+  if (j.form == kPerToken) {
+    constexpr int GPR = kHeadDim / G;                    // groups per row
+    if (idx >= BH * n_rows * GPR) return;
+    const int g = (int)(idx % GPR);
+    const long long row = j.row_begin + (idx / GPR) % n_rows;
+    const long long bh = idx / (GPR * n_rows);
+    bool from_new;
+    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G;
+    float x[G];
+#pragma unroll
+    for (int v = 0; v < G / 8; ++v) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(src + v * 8);
+      const __half* h = reinterpret_cast<const __half*>(&raw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[v * 8 + e] = h2f(h[e]);
+    }
+    if (from_new && j.normalise) {
+      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G;
+#pragma unroll
+      for (int i = 0; i < G; ++i) x[i] = h2f(__float2half_rn(x[i] * inv[i]));
+    }
+    uint32_t words[W];
+    __half s, z;
+    quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8) + g * W;
+#pragma unroll
+    for (int i = 0; i < W; ++i) dst[i] = words[i];
+    const long long so = (bh * a.capacity + row) * GPR + g;
+    j.scales[so] = s;
+    if (j.zeros) j.zeros[so] = z;
+  } else if (j.form == kPerChannel) {
+    const long long n_groups = n_rows / G;
+    if (idx >= BH * n_groups * kHeadDim) return;
+    const int c = (int)(idx % kHeadDim);
+    const long long tg = j.row_begin / G + (idx / kHeadDim) % n_groups;   // token-group index in the store
+    const long long bh = idx / (kHeadDim * n_groups);
+    float x[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      bool from_new;
+      const __half* src = token_row(j, a, bh, a.w_sink + tg * G + i, from_new);
+      float v = h2f(src[c]);
+      if (from_new && j.normalise) v = h2f(__float2half_rn(v * a.inv_norm[(bh % a.n_kv_heads) * kHeadDim + c]));
+      x[i] = v;
+    }
+    uint32_t words[W];
+    __half s, z;
+    quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+    const long long go = (bh * (a.capacity / G) + tg) * kHeadDim + c;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes) + go * W;
+#pragma unroll
+    for (int i = 0; i < W; ++i) dst[i] = words[i];
+    j.scales[go] = s;
+    if (j.zeros) j.zeros[go] = z;
+  } else {
+    // fp16 "store": copy the rows, 8 halfs per thread
+    constexpr int CPR = kHeadDim / 8;
+    if (idx >= BH * n_rows * CPR) return;
+    const int ch = (int)(idx % CPR);
+    const long long row = j.row_begin + (idx / CPR) % n_rows;
+    const long long bh = idx / (CPR * n_rows);
+    bool from_new;
+    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + ch * 8;
+    uint4 raw = *reinterpret_cast<const uint4*>(src);
+    if (from_new && j.normalise) {
+      __half* h = reinterpret_cast<__half*>(&raw);
+      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
+    }
+    __half* dst = reinterpret_cast<__half*>(j.codes) + (bh * a.capacity + row) * kHeadDim + ch * 8;
+    *reinterpret_cast<uint4*>(dst) = raw;
+  }
+}
+
+// New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
+// ring -- unless this same call already moved them on to the quantised store.
+__global__ void __launch_bounds__(256) window_copy_kernel(QuantArgs a) {
+  const QuantTensorJob& j = a.job[blockIdx.y];
+  constexpr int CPR = kHeadDim / 8;
+  const long long BH = (long long)a.batch * a.n_kv_heads;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= BH * a.t_new * CPR) return;
+  const int ch = (int)(idx % CPR);
+  const long long i = (idx / CPR) % a.t_new;
+  const long long bh = idx / (CPR * a.t_new);
+  const long long t = a.n_old + i;
+  __half* dst;
+  if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
+  else if (t >= j.ring_from) dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
+  else return;
+  uint4 raw = *reinterpret_cast<const uint4*>(j.x_new + (bh * a.t_new + i) * kHeadDim + ch * 8);
+  if (j.normalise) {
+    __half* h = reinterpret_cast<__half*>(&raw);
+    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
+  }
+  *reinterpret_cast<uint4*>(dst + ch * 8) = raw;
+}
+
+template <int G, int BITS>
+hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
+  const long long BH = (long long)a.batch * a.n_kv_heads;
+  long long threads = 0;
+  for (int w = 0; w < 2; ++w) {
+    const QuantTensorJob& j = a.job[w];
+    const long long rows = j.row_end - j.row_begin;
+    if (rows <= 0) continue;
+    long long n = 0;
+    if (j.form == kPerToken) n = BH * rows * (kHeadDim / G);
+    else if (j.form == kPerChannel) n = BH * (rows / G) * kHeadDim;
+    else n = BH * rows * (kHeadDim / 8);
+    threads = n > threads ? n : threads;
+  }
+  if (threads > 0) {
+    dim3 grid((unsigned)((threads + 255) / 256), 2);
+    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const long long cthreads = BH * a.t_new * (kHeadDim / 8);
+  dim3 grid((unsigned)((cthreads + 255) / 256), 2);
+  window_copy_kernel<<<grid, 256, 0, stream>>>(a);
+  return hipGetLastError();
+}
+
+// ---- key-norm calibration (Section "Per-channel Normalization of K") ----------------------
+
+__global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// max |K| per (kv head, channel): each work-group scans a slice of tokens of one (b, hk) and
+// folds its 128 channel maxima into the table with an unsigned atomic max on the float bits
+// (monotone for non-negative floats).
+constexpr int kCalibRows = 16;     // token rows read per pass by a 256-thread group
+__global__ void __launch_bounds__(256) absmax_kernel(const __half* __restrict__ k, int n_kv_heads,
+                                                     long long n_tokens, long long tokens_per_block,
+                                                     uint32_t* table) {
+  const long long bh = blockIdx.y;
+  const int hk = (int)(bh % n_kv_heads);
+  const int ch = threadIdx.x % 16, r = threadIdx.x / 16;
+  const long long t0 = (long long)blockIdx.x * tokens_per_block;
+  long long t1 = t0 + tokens_per_block;
+  if (t1 > n_tokens) t1 = n_tokens;
+  float m[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m[e] = 0.f;
+  for (long long t = t0 + r; t < t1; t += kCalibRows) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(k + (bh * n_tokens + t) * kHeadDim + ch * 8);
+    const __half* h = reinterpret_cast<const __half*>(&raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m[e] = fmaxf(m[e], fabsf(__half2float(h[e])));
+  }
+  __shared__ float red[kCalibRows][kHeadDim];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[r][ch * 8 + e] = m[e];
+  __syncthreads();
+  if (threadIdx.x < kHeadDim) {
+    float v = 0.f;
+    for (int i = 0; i < kCalibRows; ++i) v = fmaxf(v, red[i][threadIdx.x]);
+    atomicMax(table + hk * kHeadDim + threadIdx.x, __float_as_uint(v));
+  }
+}
+
+// One thread per channel: read every head's maximum first, then write norm and 1/norm
+// (the maxima table aliases inv_out).
+__global__ void norm_finalize_kernel(uint32_t* table, int n_kv_heads, int per_head, float* norm_out,
+                                     float* inv_out) {
+  const int c = threadIdx.x;
+  float all = 0.f;
+  for (int h = 0; h < n_kv_heads; ++h) all = fmaxf(all, __uint_as_float(table[h * kHeadDim + c]));
+  for (int h = 0; h < n_kv_heads; ++h) {
+    const float v = per_head ? __uint_as_float(table[h * kHeadDim + c]) : all;
+    const float n = v == 0.f ? 1.f : sqrtf(v);
+    norm_out[h * kHeadDim + c] = n;
+    inv_out[h * kHeadDim + c] = 1.0f / n;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream) {
+  if (a.bits == 2 && a.group == 32) return launch_quantize_t<32, 2>(a, stream);
+  if (a.bits == 2 && a.group == 64) return launch_quantize_t<64, 2>(a, stream);
+  if (a.bits == 4 && a.group == 32) return launch_quantize_t<32, 4>(a, stream);
+  if (a.bits == 4 && a.group == 64) return launch_quantize_t<64, 4>(a, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_calibrate(const __half* k, int batch, int n_kv_heads, long long n_tokens, int per_head,
+                            float* norm_out, float* inv_out, hipStream_t stream) {
+  uint32_t* table = reinterpret_cast<uint32_t*>(inv_out);
+  const int n = n_kv_heads * kHeadDim;
+  fill_u32_kernel<<<(n + 255) / 256, 256, 0, stream>>>(table, n, 0u);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long tokens_per_block = 1024;
+  dim3 grid((unsigned)((n_tokens + tokens_per_block - 1) / tokens_per_block), (unsigned)(batch * n_kv_heads));
+  absmax_kernel<<<grid, 256, 0, stream>>>(k, n_kv_heads, n_tokens, tokens_per_block, table);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  norm_finalize_kernel<<<1, kHeadDim, 0, stream>>>(table, n_kv_heads, per_head, norm_out, inv_out);
+  return hipGetLastError();
+}
+
+}  // namespace innerq

@@ -23,3 +23,82 @@ CACHE_FIELDS = ("k_codes", "k_scales", "k_zeros", "v_codes", "v_scales", "v_zero
 def bits_view(a: np.ndarray) -> np.ndarray:
     """Reinterpret fp16 as uint16 so that -0.0 / +0.0 and NaN payloads compare by bits."""
     return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+# ---------------------------------------------------------------------------
+# GPU side (imported lazily so that CPU-only test modules never need torch.cuda)
+# ---------------------------------------------------------------------------
+def gpu_config(o: orc.Config):
+    from paper_2602_23200_amd import binding as iq
+    return iq.make_config(o.batch, o.n_q_heads, o.n_kv_heads, o.head_dim, o.bits, o.group, o.w_sink,
+                          o.w_recent, o.k_mode, o.v_mode, o.sym_denominator, o.kind, o.capacity_tokens)
+
+
+def gpu_buffer_as_numpy(gcache, o: orc.Config, name: str):
+    """Download one device buffer shaped and typed like the oracle's buffer of that name."""
+    buf = gcache.buffers[name]
+    if buf is None:
+        return None
+    which = name[0]
+    raw = buf.cpu().numpy()
+    B, H, d = o.batch, o.n_kv_heads, o.head_dim
+    if name.endswith("codes"):
+        cs, ss = orc._store_shapes(o, which)
+        return raw.view(np.float16).reshape(cs) if ss is None else raw.reshape(cs)
+    if name.endswith("scales") or name.endswith("zeros"):
+        _, ss = orc._store_shapes(o, which)
+        return raw.view(np.float16).reshape(ss)
+    if name.endswith("sink"):
+        return raw.view(np.float16).reshape(B, H, o.w_sink, d)
+    return raw.view(np.float16).reshape(B, H, o.ring_slots(which), d)
+
+
+def assert_cache_equal(gcache, ocache, o: orc.Config, bsel=slice(None), hsel=slice(None), what=""):
+    """Bit-exact comparison of every live part of the GPU cache against the oracle cache.
+
+    bsel / hsel select the (batch, kv-head) slab of the GPU buffers that the oracle cache
+    (possibly built for a single slab) corresponds to.
+    """
+    N = ocache.n_tokens
+    assert gcache.n_tokens == N
+    for x in "kv":
+        n_s, n_q, n_r = orc.partition(o, x, N)
+        form = o.form(x)
+        rows = n_q // o.group if form == orc.FORM_PER_CHANNEL else n_q
+        for part in ("codes", "scales", "zeros"):
+            name = f"{x}_{part}"
+            want = getattr(ocache, name)
+            got = gpu_buffer_as_numpy(gcache, o if bsel == slice(None) else _full_cfg(gcache, o), name)
+            if want is None:
+                continue
+            if got is None:
+                # symmetric tensors keep no zero-points on the device; the oracle's are all +0
+                assert part == "zeros" and not want.view(np.uint16).any()
+                continue
+            g = got[bsel, hsel][:, :, :rows]          # store rows run along axis 2 in every form
+            w_ = want[:, :, :rows]
+            assert np.array_equal(bits_view(np.ascontiguousarray(g)), bits_view(np.ascontiguousarray(w_))), \
+                f"{what} {name} differs"
+        sink_g = gpu_buffer_as_numpy(gcache, o if bsel == slice(None) else _full_cfg(gcache, o), f"{x}_sink")
+        if sink_g is not None and n_s:
+            assert np.array_equal(bits_view(np.ascontiguousarray(sink_g[bsel, hsel][:, :, :n_s])),
+                                  bits_view(getattr(ocache, f"{x}_sink")[:, :, :n_s])), f"{what} {x}_sink"
+        ring_g = gpu_buffer_as_numpy(gcache, o if bsel == slice(None) else _full_cfg(gcache, o), f"{x}_recent")
+        ring_o = getattr(ocache, f"{x}_recent")
+        live = [t % ring_o.shape[2] for t in range(n_s + n_q, N)]
+        assert np.array_equal(bits_view(np.ascontiguousarray(ring_g[bsel, hsel][:, :, live])),
+                              bits_view(np.ascontiguousarray(ring_o[:, :, live]))), f"{what} {x}_recent"
+
+
+def _full_cfg(gcache, o: orc.Config) -> orc.Config:
+    """Oracle-style config with the GPU cache's full batch / head counts (for reshaping)."""
+    from dataclasses import replace
+    c = gcache.cfg
+    return replace(o, batch=c.batch, n_kv_heads=c.n_kv_heads, n_q_heads=c.n_q_heads)
+
+
+def max_rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """max_i |got - want| / max_i |want| per (batch, head) row, maximum over rows."""
+    num = np.abs(got.astype(np.float64) - want).max(axis=-1)
+    den = np.abs(want).max(axis=-1)
+    return float((num / den).max())

@@ -1,0 +1,274 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Integer / byte / flag results (packed codes, fp16 scale and zero-point bits, window
+contents) must be bit-exact; attention outputs must be within 2e-3 of the oracle,
+measured as max|got - want| / max|want| per (batch, head) row.
+"""
+import numpy as np
+import pytest
+
+from oracle import innerq_oracle as orc
+from paper_2602_23200_amd import workloads as wl
+from tests.helpers import (assert_cache_equal, gpu_buffer_as_numpy, gpu_config, max_rel_err,
+                           oracle_config)
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2602_23200_amd import binding as iq
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    iq.lib()
+    return torch, iq
+
+
+def small(**kw):
+    base = dict(name="s", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, n_tokens=700,
+                bits=2, group=32, w_sink=4, w_recent=48, seed=31, key_dist="student_t")
+    base.update(kw)
+    return wl.Workload(**base)
+
+
+def to_dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+KINDS = [orc.KIND_INNER, orc.KIND_OUTER, orc.KIND_FP16]
+QUANT_CASES = [(2, 32, orc.HYBRID), (2, 64, orc.HYBRID), (4, 32, orc.HYBRID), (4, 64, orc.ASYM),
+               (2, 32, orc.SYM), (4, 32, orc.SYM)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("bits,group,mode", QUANT_CASES)
+def test_bulk_append_bit_exact(env, kind, bits, group, mode):
+    torch, iq = env
+    if kind == orc.KIND_FP16 and (bits, group, mode) != QUANT_CASES[0]:
+        pytest.skip("fp16 cache does not depend on the quantiser settings")
+    w = small(bits=bits, group=group, k_mode=mode, v_mode=mode)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    want = orc.cache_init_prefill(o, K, V)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K), to_dev(torch, V))
+    torch.cuda.synchronize()
+    assert_cache_equal(g, want, o, what=f"kind{kind} b{bits} G{group} m{mode}")
+    if mode == orc.HYBRID and kind != orc.KIND_FP16:
+        M = np.signbit(gpu_buffer_as_numpy(g, o, "v_scales"))
+        assert M.any() and not M.all()          # both branches of the hybrid rule were exercised
+
+
+@pytest.mark.parametrize("sym_den", [0, 1])
+def test_symmetric_denominator_readings_bit_exact(env, sym_den):
+    torch, iq = env
+    w = small(k_mode=orc.SYM, v_mode=orc.HYBRID, n_tokens=300)
+    o = oracle_config(w, sym_denominator=sym_den)
+    K, V = wl.kv_full(w)
+    want = orc.cache_init_prefill(o, K, V)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K), to_dev(torch, V))
+    torch.cuda.synchronize()
+    assert_cache_equal(g, want, o)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_incremental_appends_bit_exact_and_chunking_independent(env, kind):
+    """Prefill chunk, then single-token decode steps across several evictions and value spills,
+    then a ragged multi-token chunk: every stage equals the oracle's token-by-token cache."""
+    torch, iq = env
+    w = small(n_tokens=420, group=32, w_recent=40)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    Kd, Vd = to_dev(torch, K), to_dev(torch, V)
+    want = orc.cache_new(o)
+    g = iq.allocate_cache(gpu_config(o))
+    pos = 0
+    for step in [3, 1, 1, 60, 1] + [1] * 150 + [37, 1, 1, 100, 1, 1]:
+        if pos + step > w.n_tokens:
+            break
+        orc.quantize_append(o, want, K[:, :, pos:pos + step], V[:, :, pos:pos + step])
+        iq.innerq_quantize_append(g, Kd[:, :, pos:pos + step].contiguous(), Vd[:, :, pos:pos + step].contiguous())
+        pos += step
+        if step != 1 or pos % 16 == 0:
+            torch.cuda.synchronize()
+            assert_cache_equal(g, want, o, what=f"after {pos} tokens")
+    torch.cuda.synchronize()
+    assert_cache_equal(g, want, o, what="final")
+    bulk = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(bulk, Kd[:, :, :pos].contiguous(), Vd[:, :, :pos].contiguous())
+    torch.cuda.synchronize()
+    assert_cache_equal(bulk, want, o, what="bulk")
+
+
+@pytest.mark.parametrize("per_head", [False, True])
+def test_calibrate_key_norm_exact(env, per_head):
+    torch, iq = env
+    w = small(n_tokens=2500, batch=3, n_kv_heads=4, n_q_heads=8)
+    o = oracle_config(w)
+    K, _ = wl.kv_full(w)
+    K[:, 1, :, 17] = 0                                   # a dead channel -> norm 1
+    want_n, want_i = orc.calibrate_key_norm(K, per_head)
+    n, i = iq.innerq_calibrate_key_norm(gpu_config(o), to_dev(torch, K), per_head)
+    torch.cuda.synchronize()
+    assert np.array_equal(n.cpu().numpy(), want_n)
+    assert np.array_equal(i.cpu().numpy(), want_i)
+
+
+def run_attention(torch, iq, o, K, V, q, k_inv_norm=None, q_scale=None, fp16_out=False):
+    g = iq.allocate_cache(gpu_config(o))
+    inv = None if k_inv_norm is None else to_dev(torch, k_inv_norm)
+    iq.innerq_quantize_append(g, to_dev(torch, K), to_dev(torch, V), k_inv_norm=inv)
+    ws = iq.allocate_workspace(g.cfg)
+    out = torch.empty(q.shape, dtype=torch.float16, device="cuda") if fp16_out else None
+    qs = None if q_scale is None else to_dev(torch, q_scale)
+    out = iq.innerq_decode_attention(g, to_dev(torch, q), ws, out=out, q_scale=qs)
+    torch.cuda.synchronize()
+    return g, out.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("bits,group,mode", QUANT_CASES)
+def test_attention_small_all_variants(env, kind, bits, group, mode):
+    torch, iq = env
+    if kind == orc.KIND_FP16 and (bits, group, mode) != QUANT_CASES[0]:
+        pytest.skip("fp16 cache does not depend on the quantiser settings")
+    w = small(bits=bits, group=group, k_mode=mode, v_mode=mode, n_tokens=1237)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("n_tokens", [1, 2, 4, 5, 51, 52, 53, 83, 84, 85, 116, 117, 180])
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
+def test_attention_edge_lengths(env, kind, n_tokens):
+    """Below, at and just above every boundary: sink only, windows only, first evicted key,
+    first value spill (w_sink 4, w_recent 48, G 32)."""
+    torch, iq = env
+    w = small(n_tokens=n_tokens)
+    o = oracle_config(w, kind=kind, capacity=256)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("heads", [(4, 4), (2, 1), (16, 2), (12, 4)])
+def test_attention_head_ratios(env, heads):
+    torch, iq = env
+    hq, hk = heads
+    w = small(n_q_heads=hq, n_kv_heads=hk, n_tokens=600)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+def test_attention_no_sink_window(env):
+    torch, iq = env
+    w = small(w_sink=0, n_tokens=500)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+def test_attention_after_decode_steps_and_fp16_output(env):
+    """Attention right after single-token appends (ring wrapped several times), fp16 output."""
+    torch, iq = env
+    w = small(n_tokens=400, w_recent=40)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want_cache = orc.cache_new(o)
+    orc.quantize_append(o, want_cache, K, V)
+    want = orc.decode_attention(o, want_cache, q)
+    g = iq.allocate_cache(gpu_config(o))
+    Kd, Vd = to_dev(torch, K), to_dev(torch, V)
+    iq.innerq_quantize_append(g, Kd[:, :, :250].contiguous(), Vd[:, :, :250].contiguous())
+    for t in range(250, 400):
+        iq.innerq_quantize_append(g, Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous())
+    ws = iq.allocate_workspace(g.cfg)
+    out32 = iq.innerq_decode_attention(g, to_dev(torch, q), ws)
+    out16 = torch.empty(q.shape, dtype=torch.float16, device="cuda")
+    iq.innerq_decode_attention(g, to_dev(torch, q), ws, out=out16)
+    torch.cuda.synchronize()
+    assert max_rel_err(out32.cpu().numpy(), want) <= TOL
+    assert max_rel_err(out16.float().cpu().numpy(), want) <= TOL + 2.0 ** -10
+
+
+def test_key_norm_unfolded_path_matches_oracle_and_folded(env):
+    torch, iq = env
+    w = small(n_tokens=900)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    norm, inv = orc.calibrate_key_norm(K, per_head=True)
+    want_cache = orc.cache_init_prefill(o, K, V, k_inv_norm=inv)
+    want = orc.decode_attention(o, want_cache, q, q_scale=norm)
+    g, got = run_attention(torch, iq, o, K, V, q, k_inv_norm=inv, q_scale=norm)
+    assert_cache_equal(g, want_cache, o)
+    assert max_rel_err(got, want) <= TOL
+    Kf, qf = orc.apply_channel_scale(K, inv), orc.apply_channel_scale(q, norm)
+    g2, got2 = run_attention(torch, iq, o, Kf, V, qf)
+    assert_cache_equal(g2, want_cache, o)
+    assert np.array_equal(got, got2)
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama2_7b_4k"])
+def test_attention_baseline_configs_full(env, name):
+    torch, iq = env
+    w = wl.WORKLOADS[name]
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want_cache = orc.cache_init_prefill(o, K, V)
+    want = orc.decode_attention(o, want_cache, q)
+    g, got = run_attention(torch, iq, o, K, V, q)
+    assert_cache_equal(g, want_cache, o)
+    assert max_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("name,slabs", [("llama3_8b_32k", [(0, 0), (3, 5), (7, 7)]),
+                                         ("mistral_7b_8k", [(0, 0), (17, 3), (31, 7)])])
+def test_attention_baseline_configs_full_size_sampled(env, name, slabs):
+    """Full-size cache on the GPU in the launch configuration the benchmark times; the oracle
+    recomputes sampled (batch, kv-head) slabs on their own: packed bytes bit-exact, outputs in tolerance."""
+    torch, iq = env
+    w = wl.WORKLOADS[name]
+    o = oracle_config(w)
+    B, Hk, N, d = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim
+    Kd = torch.empty((B, Hk, N, d), dtype=torch.float16, device="cuda")
+    Vd = torch.empty_like(Kd)
+    keep = {}
+    for b in range(B):
+        for h in range(Hk):
+            k, v = wl.kv_slab(w, b, h)
+            Kd[b, h].copy_(torch.from_numpy(k))
+            Vd[b, h].copy_(torch.from_numpy(v))
+            if (b, h) in slabs:
+                keep[(b, h)] = (k, v)
+    q = wl.query(w)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, Kd, Vd)
+    ws = iq.allocate_workspace(g.cfg)
+    got = iq.innerq_decode_attention(g, to_dev(torch, q), ws)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert np.isfinite(got).all()
+    r = w.n_q_heads // w.n_kv_heads
+    o1 = oracle_config(w.with_(batch=1, n_kv_heads=1, n_q_heads=r))
+    for (b, h), (k, v) in keep.items():
+        want_cache = orc.cache_init_prefill(o1, k[None, None], v[None, None])
+        assert_cache_equal(g, want_cache, o1, bsel=slice(b, b + 1), hsel=slice(h, h + 1), what=f"slab {b},{h}")
+        want = orc.decode_attention(o1, want_cache, q[b:b + 1, h * r:(h + 1) * r])
+        assert max_rel_err(got[b:b + 1, h * r:(h + 1) * r], want) <= TOL
