@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the InnerQ decode-attention hot path on one MI355X.
+
+One "step" = one decode step of one attention layer over the whole batch:
+innerq_quantize_append of the new token (key evicted and quantised every step,
+values spilled G at a time) followed by innerq_decode_attention over the whole
+cache.  Inputs are synthetic, seeded, generated on the device, and resident in
+HBM before the timed region.  Several distinct cache instances are rotated so a
+timed step never re-reads bytes the previous step left in the 256 MB
+last-level cache.
+
+Prints ONE JSON line (metric / value / roofline / cpu_baseline ...).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--workload", default="llama3_8b_32k")
+    p.add_argument("--kind", default="inner", choices=["inner", "outer", "fp16"])
+    p.add_argument("--k-mode", default=None, choices=["sym", "asym", "hybrid"])
+    p.add_argument("--v-mode", default=None, choices=["sym", "asym", "hybrid"])
+    p.add_argument("--instances", type=int, default=8, help="distinct caches rotated through the timed steps")
+    p.add_argument("--layers", type=int, default=None, help="layers per step (default: the workload's)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-seconds", type=float, default=12.0)
+    return p.parse_args()
+
+
+class Hip:
+    """The handful of HIP runtime calls the benchmark makes itself (events on the launch stream)."""
+
+    def __init__(self):
+        self.rt = C.CDLL("libamdhip64.so")
+        self.rt.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.rt.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def event(self) -> int:
+        e = C.c_void_p()
+        assert self.rt.hipEventCreate(C.byref(e)) == 0
+        return e.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = C.c_float()
+        assert self.rt.hipEventElapsedTime(C.byref(ms), a, b) == 0
+        return ms.value
+
+
+def algorithmic_bytes(w, cfg, iq, n_tokens):
+    """Bytes the method itself must move per attention call over the quantised range:
+    per cached (token, kv-head) K + V codes, fp16 scales and (unless symmetric) fp16 zero-points."""
+    nq_k = iq.innerq_partition(cfg, 0, n_tokens)[1]
+    nq_v = iq.innerq_partition(cfg, 1, n_tokens)[1]
+    n_both = min(nq_k, nq_v)
+    d, b, G = w.head_dim, cfg.bits, cfg.group
+    if cfg.kind == iq.KIND_FP16:
+        per_unit = 2 * d * 2
+    else:
+        per_unit = 0
+        for mode in (cfg.k_mode, cfg.v_mode):
+            per_unit += d * b // 8 + (d // G) * 2 * (1 if mode == iq.SYM else 2)
+    units = w.batch * w.n_kv_heads * n_both
+    return per_unit, units
+
+
+def make_instance(torch, iq, w, cfg, layer, n_prefill, gen):
+    """One cache filled with n_prefill synthetic tokens (values per the workload recipe, drawn on the device)."""
+    B, Hk, d = w.batch, w.n_kv_heads, w.head_dim
+    from paper_2602_23200_amd import workloads as wl
+    sigma = torch.from_numpy(wl.key_channel_sigma(w, layer)).to("cuda", torch.float32)      # [Hk, d]
+    cache = iq.allocate_cache(cfg)
+    k = torch.randn((B, Hk, n_prefill, d), device="cuda", generator=gen)
+    k.mul_(sigma[None, :, None, :])
+    k = k.half()
+    v = torch.randn((B, Hk, n_prefill, d), device="cuda", generator=gen).half()
+    inv = None
+    if w.fold_key_norm:
+        # the factors are folded into the projections at the end of prefill; the prefill keys
+        # that already exist are divided on their way into the cache
+        _, inv = iq.innerq_calibrate_key_norm(cfg, k, per_head=False)
+    iq.innerq_quantize_append(cache, k, v, k_inv_norm=inv)
+    del k, v
+    torch.cuda.synchronize()
+    return cache
+
+
+def cpu_baseline(w, kind_id, seconds):
+    """The CPU oracle timed on a bounded sample of the same workload: whole (batch, kv-head) slabs,
+    each one decode step (append one token + attention for the slab's query heads)."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    from oracle import innerq_oracle as orc
+    from paper_2602_23200_amd import workloads as wl
+
+    r = w.n_q_heads // w.n_kv_heads
+    w1 = w.with_(batch=1, n_kv_heads=1, n_q_heads=r)
+    cap = -(-(w.n_tokens + 2 * w.group) // w.group) * w.group
+    o = orc.Config(1, r, 1, w.head_dim, w.bits, w.group, w.w_sink, w.w_recent, w.k_mode, w.v_mode, 0,
+                   kind_id, cap)
+    total_slabs = w.batch * w.n_kv_heads * w.n_layers
+    done, spent, wall0 = 0, 0.0, time.perf_counter()
+    with threadpool_limits(limits=1):
+        # bounded: stop after `seconds` of timed oracle work or ~4x that of wall-clock (the untimed
+        # set-up of a slab, quantising its prefill, costs more than the timed decode step)
+        while done < total_slabs and spent < seconds and time.perf_counter() - wall0 < 4 * seconds:
+            b, h = divmod(done % (w.batch * w.n_kv_heads), w.n_kv_heads)
+            k, v = wl.kv_slab(w, b, h, n_tokens=w.n_tokens)
+            cache = orc.cache_init_prefill(o, k[None, None, :-1], v[None, None, :-1])      # not timed: setup
+            q = wl.query(w)[b:b + 1, h * r:(h + 1) * r]
+            t0 = time.perf_counter()
+            orc.append_token(o, cache, k[None, None, -1], v[None, None, -1])
+            out = orc.decode_attention(o, cache, q)
+            spent += time.perf_counter() - t0
+            assert np.isfinite(out).all()
+            done += 1
+    step_seconds = spent / done * total_slabs            # one step = every slab of every layer once
+    return {"value": w.batch / step_seconds, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} of {total_slabs} (batch, kv-head) slabs of {w.name}, one decode step each "
+                      f"(append + attention, {w.n_tokens} cached tokens), numpy float64, 1 thread, "
+                      f"{spent:.1f} s measured, scaled to the full step"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2602_23200_amd import binding as iq
+    from paper_2602_23200_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    w = wl.WORKLOADS[args.workload]
+    modes = {"sym": iq.SYM, "asym": iq.ASYM, "hybrid": iq.HYBRID}
+    if args.k_mode:
+        w = w.with_(k_mode=modes[args.k_mode])
+    if args.v_mode:
+        w = w.with_(v_mode=modes[args.v_mode])
+    kind_id = {"inner": iq.KIND_INNER, "outer": iq.KIND_OUTER, "fp16": iq.KIND_FP16}[args.kind]
+    n_layers = args.layers or w.n_layers
+    K, W = args.steps, args.warmup
+    # one cache per layer; single-layer workloads rotate `instances` caches instead
+    n_inst = n_layers if n_layers > 1 else max(1, args.instances)
+    per_inst_appends = -(-(K + W + 2 * K) // n_inst) + 1 if n_layers == 1 else (K + W + 2 * K) + 1
+    cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
+    cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
+                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen)
+              for i in range(n_inst)]
+    ws = iq.allocate_workspace(cfg)
+    B, Hq, Hk, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    # a pool of new tokens / queries so that consecutive steps do not reuse the same inputs
+    pool = 16
+    k_new = torch.randn((pool, B, Hk, 1, d), device="cuda", generator=gen).half()
+    v_new = torch.randn((pool, B, Hk, 1, d), device="cuda", generator=gen).half()
+    q_new = torch.randn((pool, B, Hq, d), device="cuda", generator=gen).half()
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    state = {"i": 0}
+
+    def step(profile=None):
+        """One decode step: every layer appends its new token and attends."""
+        for layer in range(n_layers):
+            i = state["i"]
+            state["i"] += 1
+            cache = caches[i % n_inst]
+            iq.innerq_quantize_append(cache, k_new[i % pool], v_new[i % pool], stream=stream)
+            if profile is not None:
+                iq.innerq_profile_next_attention(*profile[layer])
+            iq.innerq_decode_attention(cache, q_new[i % pool], ws, out=out, stream=stream)
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) / K * 1e3
+    n_ctx_end = caches[0].n_tokens
+
+    # second pass of K steps with HIP events around the dominant kernel of every attention call
+    hip = Hip()
+    evs = [[(hip.event(), hip.event()) for _ in range(n_layers)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for s in range(K):
+        step(profile=evs[s])
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    durs = [hip.elapsed_ms(a, b) for per_step in evs for (a, b) in per_step]
+    kern_ms = sum(durs) / len(durs)
+    durs_sorted = sorted(durs)
+    kern_ms_median = durs_sorted[len(durs) // 2]
+
+    # attention-only and append-only timings (reported, not the headline)
+    def time_only(fn, n):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) / n * 1e3
+
+    def attn_only():
+        i = state["i"]
+        state["i"] += 1
+        iq.innerq_decode_attention(caches[i % n_inst], q_new[i % pool], ws, out=out, stream=stream)
+
+    def append_only():
+        i = state["i"]
+        state["i"] += 1
+        iq.innerq_quantize_append(caches[i % n_inst], k_new[i % pool], v_new[i % pool], stream=stream)
+
+    attn_ms = time_only(attn_only, K) * n_layers
+    append_ms = time_only(append_only, K) * n_layers
+
+    per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
+    alg_bytes = per_unit * units
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    traffic = None
+    prof_json = os.path.join(ROOT, "profiles", f"traffic_{w.name}_{args.kind}.json")
+    if os.path.exists(prof_json):
+        traffic = json.load(open(prof_json)).get("hbm_bytes_per_launch")
+
+    result = {
+        "metric": "decode-attention tokens/s (one attention layer step: quantize_append + decode_attention, "
+                  "2-bit/4-bit inner-grouped KV) + achieved HBM GB/s of the fused kernel (% of peak)"
+                  if n_layers == 1 else
+                  "decode tokens/s over all layers (quantize_append + decode_attention per layer) + achieved HBM GB/s",
+        "value": B / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "kind": args.kind, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
+                   "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
+                   "group": w.group, "w_sink": w.w_sink, "w_recent": w.w_recent,
+                   "k_mode": ["sym", "asym", "hybrid"][w.k_mode], "v_mode": ["sym", "asym", "hybrid"][w.v_mode],
+                   "layers": n_layers, "cache_instances": n_inst},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "fused dequant score+value pass over the quantised range",
+                     "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_ms_median,
+                     "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_token_kvhead": per_unit,
+                     "token_kvheads_per_launch": units},
+        "breakdown_ms": {"step": ms_per_step, "step_with_events": (t3 - t2) / K * 1e3,
+                         "attention_only": attn_ms, "append_only": append_ms},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, kind_id, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -178,6 +178,15 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Measurement hook (no counterpart in the paper; its Section "Latency" times the fused
+ * dequantise-and-multiply kernels on their own, and this lets a benchmark do the same).
+ * The next innerq_decode_attention call made by the calling host thread records
+ * ev_start immediately before and ev_stop immediately after the launch of its dominant
+ * kernel (the fused dequantise + score + value pass over the quantised range) on that
+ * call's stream.  Both are hipEvent_t created by the caller with timing enabled; the
+ * request is consumed by that one call.  Passing NULL for either cancels a pending request. */
+int innerq_profile_next_attention(void *ev_start, void *ev_stop);
+
 #ifdef __cplusplus
 }
 #endif

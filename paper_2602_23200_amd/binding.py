@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.innerq_decode_attention.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.innerq_decode_attention.restype = C.c_int
+        L.innerq_profile_next_attention.argtypes = [C.c_void_p, C.c_void_p]
+        L.innerq_profile_next_attention.restype = C.c_int
         _lib = L
     return _lib
 
@@ -191,3 +193,8 @@ def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, 
     if st != OK:
         raise InnerQError(st, "innerq_decode_attention")
     return out
+
+
+def innerq_profile_next_attention(ev_start: Optional[int], ev_stop: Optional[int]) -> None:
+    """ev_start / ev_stop: raw hipEvent_t handles (ints), or None to cancel."""
+    lib().innerq_profile_next_attention(ev_start, ev_stop)

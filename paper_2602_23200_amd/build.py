@@ -17,6 +17,7 @@ SOURCES = {
     "api.hip": [],
     "quantize.hip": ["-ffp-contract=off"],
     "attention_generic.hip": [],
+    "attention_inner.hip": ["-save-temps=obj"] if os.environ.get("INNERQ_SAVE_TEMPS") else [],
 }
 
 

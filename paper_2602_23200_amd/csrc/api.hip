@@ -78,9 +78,31 @@ TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which,
   return v;
 }
 
+// Compute units of the current device (queried once per device; a host-side attribute read).
+int compute_units() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
 }  // namespace
 
 extern "C" {
+
+int innerq_profile_next_attention(void* ev_start, void* ev_stop) {
+  const bool on = ev_start && ev_stop;
+  g_prof_start = on ? static_cast<hipEvent_t>(ev_start) : nullptr;
+  g_prof_stop = on ? static_cast<hipEvent_t>(ev_stop) : nullptr;
+  return INNERQ_OK;
+}
 
 int innerq_validate_config(const innerq_config_t* cfg) { return check_config(cfg); }
 
@@ -226,7 +248,17 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   const long long win_tokens = n_sink + (win_b1 - win_b0);
   const int r = c.n_q_heads / c.n_kv_heads;
   int n_splits = 0;
-  if (n_both > 0) {
+  const bool fused = attention_inner_supported(a);
+  if (n_both > 0 && fused) {
+    // one wavefront per split; aim at two resident wavefronts per SIMD over the whole chip
+    const long long slots = (long long)compute_units() * 4 * 2;
+    long long s = slots / ((long long)c.batch * c.n_kv_heads);
+    const long long n_tiles = ceil_div(n_both, 64);
+    if (s > n_tiles) s = n_tiles;
+    if (s > split_cap(c)) s = split_cap(c);
+    if (s < 1) s = 1;
+    n_splits = (int)s;
+  } else if (n_both > 0) {
     const long long blocks_per_split = (long long)c.batch * c.n_kv_heads * ceil_div(r, kHeadTile);
     long long s = ceil_div(2048, blocks_per_split);
     const long long by_len = ceil_div(n_both, 128);
@@ -243,8 +275,13 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   a.ws_o = a.ws_ml + ((heads * a.n_partials * 2 + 3) / 4) * 4;
 
   hipError_t e = hipSuccess;
+  hipEvent_t prof_start = g_prof_start, prof_stop = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
   if (n_splits > 0) {
-    e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+    if (prof_start) (void)hipEventRecord(prof_start, stream);
+    if (fused) e = launch_attention_inner(a, n_both, n_splits, stream);
+    else e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+    if (prof_stop) (void)hipEventRecord(prof_stop, stream);
     if (e != hipSuccess) return INNERQ_E_HIP;
   }
   if (n_win > 0) {

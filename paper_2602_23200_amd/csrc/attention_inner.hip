@@ -1,0 +1,382 @@
+// Fused dequantise + score + softmax + value kernel for the inner-grouped cache
+// (keys per-token group-wise, values per-channel group-wise; Section "InnerQ").
+//
+// One wavefront streams a contiguous range of quantised tokens once and serves
+// every query head that shares the kv head from those bytes.
+//
+// Why the grouping matters here (Section "InnerQ", Figure "inner_outer"): with
+// groups along the inner dimension of each product, a group's scale and
+// zero-point factor out of the inner sum,
+//     q . k_j      = sum_g |S_jg| * (sum_{c in g} q_c u_jc) + Zeff_jg * (sum_{c in g} q_c)
+//     sum_j p_j v_jc = sum_T |S_Tc| * (sum_{j in T} p_j u_jc) + Zeff_Tc * (sum_{j in T} p_j)
+// (u = stored field, Zeff = Z for an asymmetric group and -|S| 2^(b-1) for a
+// symmetric one: Eq. hybrid_dequant), so the inner sums run on the raw integer
+// fields and one multiply per group applies the scale.
+//
+// Mapping to CDNA4:
+//   * inner sums run on the matrix cores with v_mfma_f32_4x4x4_16B_f16: 16
+//     independent 4x4x4 blocks per instruction, A = 4 query heads x 4 inner
+//     indices (shared by all blocks), B = 4 inner indices x 4 lanes.  In the score
+//     pass a lane owns one token, in the value pass two channels, and the result
+//     lands in the lane that holds that token's / channel's scale: no cross-lane
+//     traffic.
+//   * a b-bit field becomes an fp16 operand with ONE and per two fields: masked in
+//     place inside a 16-bit half it is the fp16 denormal u * 2^(b*pos) * 2^-24
+//     (the matrix cores keep fp16 denormals); the position factor is folded into
+//     the A operand (query / probabilities), the constant into the group scale.
+//   * softmax probabilities are rounded to fp16 for the value pass and the
+//     normaliser is the MFMA sum of those same rounded values (an extra all-ones B
+//     operand), so the weights stay consistent.
+#include "innerq_dev.h"
+
+namespace innerq {
+namespace {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = kHeadDim;
+constexpr int TILE = 64;                       // tokens per wave iteration (one per lane)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSmScale = 0.08838834764831845f;   // 1/sqrt(128)
+
+template <int BITS>
+struct Fields {
+  static constexpr int FPW = 32 / BITS;        // fields per 32-bit word
+  static constexpr int HALF = FPW / 2;         // fields per 16-bit half
+  static constexpr int MPW = HALF / 2;         // MFMAs per word (each eats two field positions x two halves)
+  static constexpr int SH = BITS == 2 ? 10 : 8;        // one shift brings the upper fields of both halves down
+  static constexpr int NDIRECT = BITS == 2 ? 5 : 2;    // field positions that fit the fp16 mantissa unshifted
+  static __host__ __device__ constexpr int pos(int f) { return f < NDIRECT ? f : f - NDIRECT; }
+  static __host__ __device__ constexpr uint32_t mask(int f) {
+    return (uint32_t)(((1u << BITS) - 1u) * 0x00010001u) << (BITS * pos(f));
+  }
+  static __host__ __device__ constexpr uint32_t ones(int f) { return 0x00010001u << (BITS * pos(f)); }
+  // index of inner position e (0..FPW) inside its word's operand table: [mfma][slot]
+  static __host__ __device__ constexpr int slot(int e) {
+    const int hi = e / HALF, f = e % HALF;
+    return (f / 2) * 4 + (f % 2) * 2 + hi;
+  }
+};
+
+template <int BITS>
+__device__ inline half4_t operand(uint32_t w, uint32_t w_shifted, int m) {
+  using F = Fields<BITS>;
+  const int f0 = 2 * m, f1 = 2 * m + 1;
+  u32x2 r;
+  r.x = (f0 < F::NDIRECT ? w : w_shifted) & F::mask(f0);
+  r.y = (f1 < F::NDIRECT ? w : w_shifted) & F::mask(f1);
+  return __builtin_bit_cast(half4_t, r);
+}
+
+template <int BITS>
+__device__ inline half4_t ones_operand(int m) {
+  using F = Fields<BITS>;
+  u32x2 r;
+  r.x = F::ones(2 * m);
+  r.y = F::ones(2 * m + 1);
+  return __builtin_bit_cast(half4_t, r);
+}
+
+__device__ inline float wave_max(float x) {
+  // butterflies inside a row of 16 lanes via DPP, then the four rows through scalar registers
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true)));
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
+}
+
+template <typename T>
+__device__ inline T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
+
+// Everything one wave iteration reads from the quantised store.
+template <int BITS, int G>
+struct TileRegs {
+  static constexpr int KC = D * BITS / 8 / 16;         // 16-byte pieces of one key row
+  static constexpr int NG = D / G;                     // key groups per token
+  static constexpr int GPT = TILE / G;                 // value token-groups per tile
+  static constexpr int VC = 2 * G * BITS / 8 / 16;     // 16-byte pieces of two channels of one value group
+  u32x4 kc[KC];
+  uint32_t ks[NG / 2], kz[NG / 2];                     // fp16 pairs
+  u32x4 vc[GPT][VC];
+  uint32_t vs[GPT], vz[GPT];                           // fp16 pairs (this lane's two channels)
+};
+
+template <int BITS, int G, int NH4>
+__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long long n_both, int n_splits) {
+  using F = Fields<BITS>;
+  using Regs = TileRegs<BITS, G>;
+  constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC;
+  constexpr int NW = D / F::FPW;                       // words per key row
+  constexpr int WPG = G / F::FPW;                      // words per group (key: channels; value: tokens)
+  constexpr int TW = TILE / F::FPW;                    // value-side words per tile
+  constexpr int MPW = F::MPW;
+  constexpr int HALFCODE = 1 << (BITS - 1);
+  constexpr int NH = NH4 * 4;
+
+  const int lane = threadIdx.x;
+  const long long bh = blockIdx.y;
+  const int b = (int)(bh / a.n_kv_heads), hk = (int)(bh % a.n_kv_heads);
+  const int r = a.n_q_heads / a.n_kv_heads;
+  const bool has_kz = a.k.zeros != nullptr, has_vz = a.v.zeros != nullptr;
+
+  // ---- tile range of this wave
+  const long long n_tiles = (n_both + TILE - 1) / TILE;
+  const long long base_t = n_tiles / n_splits, rem_t = n_tiles % n_splits;
+  const long long s_idx = blockIdx.x;
+  const long long t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
+  const long long t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
+
+  __shared__ __attribute__((aligned(16))) _Float16 qA[NH * D];          // query operand table [head][word][mfma][slot]
+  __shared__ __attribute__((aligned(16))) float qsum[NH4][NG][4];       // log2e/sqrt(d) * sum of q over each key group
+  __shared__ __attribute__((aligned(16))) _Float16 pA[NH * TILE];       // probability operand table [head][word][mfma][slot]
+
+  // ---- query: fp16 (optionally rescaled), position factors folded in
+  for (int i = lane; i < NH * D; i += 64) {
+    const int h = i / D, c = i % D;
+    float qv = 0.f;
+    if (h < r) {
+      const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h) * D + c];
+      qv = a.q_scale ? __half2float(__float2half_rn(__half2float(qh) * a.q_scale[hk * D + c])) : __half2float(qh);
+    }
+    const int word = c / F::FPW, e = c % F::FPW;
+    const int f = e % F::HALF;
+    const float factor = (float)(1 << (4 + BITS * 4)) / (float)(1 << (BITS * F::pos(f) + BITS * 4));   // 2^(4 - b*pos)
+    qA[(h * NW + word) * (MPW * 4) + F::slot(e)] = (_Float16)(qv * factor);
+  }
+  __syncthreads();
+  if (lane < NH * NG) {
+    const int h = lane / NG, g = lane % NG;
+    // sum of the (rescaled) query over the group, undoing the position factors
+    float s = 0.f;
+    for (int c = g * G; c < (g + 1) * G; ++c) {
+      const int word = c / F::FPW, e = c % F::FPW, f = e % F::HALF;
+      const float factor = (float)(1 << (BITS * F::pos(f) + BITS * 4)) / (float)(1 << (4 + BITS * 4));
+      s += (float)qA[(h * NW + word) * (MPW * 4) + F::slot(e)] * factor;
+    }
+    qsum[h / 4][g][h % 4] = s * (kSmScale * kLog2e);
+  }
+  __syncthreads();
+
+  // ---- per-(b, hk) base pointers
+  const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * BITS / 8);
+  const __half* kscales = a.k.scales + bh * a.capacity * NG;
+  const __half* kzeros = has_kz ? a.k.zeros + bh * a.capacity * NG : nullptr;
+  const long long vgroups = a.capacity / G;
+  const uint8_t* vcodes = a.v.codes + bh * vgroups * D * (G * BITS / 8);
+  const __half* vscales = a.v.scales + bh * vgroups * D;
+  const __half* vzeros = has_vz ? a.v.zeros + bh * vgroups * D : nullptr;
+  const long long last_row = n_both - 1, last_group = n_both / G - 1;
+
+  auto load_tile = [&](long long tile, Regs& t) {
+    long long row = tile * TILE + lane;
+    row = row > last_row ? last_row : row;
+    const u32x4* kp = reinterpret_cast<const u32x4*>(kcodes + row * (D * BITS / 8));
+#pragma unroll
+    for (int i = 0; i < KC; ++i) t.kc[i] = stream_load(kp + i);
+    if constexpr (NG == 4) {
+      const u32x2 s = stream_load(reinterpret_cast<const u32x2*>(kscales + row * NG));
+      t.ks[0] = s.x; t.ks[1] = s.y;
+      if (has_kz) {
+        const u32x2 z = stream_load(reinterpret_cast<const u32x2*>(kzeros + row * NG));
+        t.kz[0] = z.x; t.kz[1] = z.y;
+      }
+    } else {
+      t.ks[0] = stream_load(reinterpret_cast<const uint32_t*>(kscales + row * NG));
+      if (has_kz) t.kz[0] = stream_load(reinterpret_cast<const uint32_t*>(kzeros + row * NG));
+    }
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+      long long grp = tile * GPT + gi;
+      grp = grp > last_group ? last_group : grp;
+      const u32x4* vp = reinterpret_cast<const u32x4*>(vcodes + (grp * D + 2 * lane) * (G * BITS / 8));
+#pragma unroll
+      for (int i = 0; i < VC; ++i) t.vc[gi][i] = stream_load(vp + i);
+      t.vs[gi] = stream_load(reinterpret_cast<const uint32_t*>(vscales + grp * D + 2 * lane));
+      if (has_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + grp * D + 2 * lane));
+    }
+  };
+
+  // ---- running softmax state (log2 domain) and output accumulators
+  float m_run[NH], l_run[NH], o[NH][2];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) { m_run[h] = -INFINITY; l_run[h] = 0.f; o[h][0] = 0.f; o[h][1] = 0.f; }
+
+  // where this lane's token sits in the probability operand table, and its position factor
+  const int p_e = lane % F::FPW;
+  const int p_index = (lane / F::FPW) * (MPW * 4) + F::slot(p_e);
+  const float p_shift = (float)(8 - BITS * F::pos(p_e % F::HALF));      // p is stored as p * 2^(8 - b*pos)
+  const int qa_lane = (lane & 3) * D;                                   // this lane supplies head (lane & 3) to A
+  const int pa_lane = (lane & 3) * TILE;
+
+  Regs cur;
+  if (t0 < t1) load_tile(t0, cur);
+  for (long long tile = t0; tile < t1; ++tile) {
+    Regs nxt;
+    if (tile + 1 < t1) load_tile(tile + 1, nxt);       // in flight while this tile is computed
+    else nxt = cur;
+
+    // ================= scores: lane = token (Eq. att:1 with Eq. hybrid_dequant fused) =================
+    float s2[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) s2[h] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      float4_t acc[NH4];
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int wd = 0; wd < WPG; ++wd) {
+        const int word = g * WPG + wd;
+        const uint32_t w = cur.kc[word / 4][word % 4], wsft = w >> F::SH;
+#pragma unroll
+        for (int m = 0; m < MPW; ++m) {
+          const half4_t bop = operand<BITS>(w, wsft, m);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPW + m) * 4]);
+            acc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[n], 0, 0, 0);
+          }
+        }
+      }
+      const uint32_t spair = cur.ks[g / 2];
+      const __half sh = __ushort_as_half((unsigned short)((g & 1) ? (spair >> 16) : (spair & 0xffffu)));
+      const float sc = __half2float(sh);
+      const bool asym = (g & 1) ? (spair >> 31) : ((spair >> 15) & 1u);
+      const float S = fabsf(sc);
+      float zeff = S * (float)(-HALFCODE);
+      if (has_kz) {
+        const uint32_t zpair = cur.kz[g / 2];
+        const float z = __half2float(__ushort_as_half((unsigned short)((g & 1) ? (zpair >> 16) : (zpair & 0xffffu))));
+        zeff = asym ? z : zeff;
+      }
+      const float tS = S * (kSmScale * kLog2e * 1048576.0f);            // 2^20 undoes the operand factors
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+        const float4_t qs = *reinterpret_cast<const float4_t*>(&qsum[n][g][0]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s2[n * 4 + i] += tS * acc[n][i] + zeff * qs[i];
+      }
+    }
+
+    // ================= running softmax (Eq. att:2), probabilities to the operand table =================
+    const bool valid = tile * TILE + lane <= last_row;
+    __syncthreads();                                   // previous tile's readers of pA are done
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const float sv = valid ? s2[h] : -INFINITY;
+      const float m_new = fmaxf(m_run[h], wave_max(sv));
+      const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);
+      m_run[h] = m_new;
+      l_run[h] *= alpha;
+      o[h][0] *= alpha;
+      o[h][1] *= alpha;
+      const float p = __builtin_amdgcn_exp2f(sv - m_new + p_shift);
+      pA[h * TILE + p_index] = (_Float16)p;
+    }
+    __syncthreads();
+
+    // ================= values: lane = two channels (Eq. att:3 with Eq. hybrid_dequant fused) =================
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+      float4_t acc0[NH4], acc1[NH4], accl[NH4];
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+        acc0[n] = float4_t{0.f, 0.f, 0.f, 0.f};
+        acc1[n] = acc0[n];
+        accl[n] = acc0[n];
+      }
+#pragma unroll
+      for (int wd = 0; wd < WPG; ++wd) {
+        const uint32_t wa = cur.vc[gi][wd / 4][wd % 4], wb = cur.vc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
+        const uint32_t was = wa >> F::SH, wbs = wb >> F::SH;
+#pragma unroll
+        for (int m = 0; m < MPW; ++m) {
+          const half4_t b0 = operand<BITS>(wa, was, m);
+          const half4_t b1 = operand<BITS>(wb, wbs, m);
+          const half4_t b1s = ones_operand<BITS>(m);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const half4_t aop =
+                *reinterpret_cast<const half4_t*>(&pA[n * 4 * TILE + pa_lane + ((gi * WPG + wd) * MPW + m) * 4]);
+            acc0[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b0, acc0[n], 0, 0, 0);
+            acc1[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1, acc1[n], 0, 0, 0);
+            accl[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1s, accl[n], 0, 0, 0);
+          }
+        }
+      }
+      const uint32_t spair = cur.vs[gi];
+      const float S0 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair & 0xffffu))));
+      const float S1 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair >> 16))));
+      float z0 = S0 * (float)(-HALFCODE), z1 = S1 * (float)(-HALFCODE);
+      if (has_vz) {
+        const uint32_t zpair = cur.vz[gi];
+        z0 = ((spair >> 15) & 1u) ? __half2float(__ushort_as_half((unsigned short)(zpair & 0xffffu))) : z0;
+        z1 = (spair >> 31) ? __half2float(__ushort_as_half((unsigned short)(zpair >> 16))) : z1;
+      }
+      const float tS0 = S0 * 65536.0f, tS1 = S1 * 65536.0f;             // 2^16 undoes the operand factors
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float psum = accl[n][i] * 65536.0f;                     // sum of the fp16 probabilities of this group
+          l_run[n * 4 + i] += psum;
+          o[n * 4 + i][0] += tS0 * acc0[n][i] + z0 * psum;
+          o[n * 4 + i][1] += tS1 * acc1[n][i] + z1 * psum;
+        }
+      }
+    }
+    cur = nxt;
+  }
+
+  // ---- partial (m, l, o) of every real head
+  const int slot = blockIdx.x;
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    if (h < r) {
+      const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
+      float2 ov;
+      ov.x = o[h][0];
+      ov.y = o[h][1];
+      *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + slot) * D + 2 * lane]) = ov;
+      if (lane == 0) {
+        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 0] = m_run[h] * kLn2;
+        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h];
+      }
+    }
+  }
+}
+
+template <int BITS, int G>
+hipError_t launch_t(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream) {
+  const int r = a.n_q_heads / a.n_kv_heads;
+  dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
+  if (r <= 4) attention_inner_kernel<BITS, G, 1><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
+  else attention_inner_kernel<BITS, G, 2><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attention_inner_supported(const AttnArgs& a) {
+  const int r = a.n_q_heads / a.n_kv_heads;
+  return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8;
+}
+
+hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream) {
+  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, stream);
+  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, stream);
+  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, stream);
+  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace innerq

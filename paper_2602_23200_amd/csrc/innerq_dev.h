@@ -95,4 +95,9 @@ hipError_t launch_attention_generic(const AttnArgs& a, long long a0, long long a
                                     int n_chunks, int first_slot, hipStream_t stream);
 hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
 
+// Fused MFMA kernel for the inner-grouped layout: tokens [w_sink, w_sink + n_both) cut into
+// n_splits contiguous ranges of 64-token tiles, one wavefront each, partial slots 0 .. n_splits.
+bool attention_inner_supported(const AttnArgs& a);
+hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream);
+
 }  // namespace innerq
