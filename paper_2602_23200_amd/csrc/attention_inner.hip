@@ -110,8 +110,8 @@ struct TileRegs {
   uint32_t vs[GPT], vz[GPT];                           // fp16 pairs (this lane's two channels)
 };
 
-template <int BITS, int G, int NH4>
-__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long long n_both, int n_splits) {
+template <int BITS, int G, int NH4, bool ZK, bool ZV>
+__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_both, int n_splits) {
   using F = Fields<BITS>;
   using Regs = TileRegs<BITS, G>;
   constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC;
@@ -126,14 +126,14 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
   const long long bh = blockIdx.y;
   const int b = (int)(bh / a.n_kv_heads), hk = (int)(bh % a.n_kv_heads);
   const int r = a.n_q_heads / a.n_kv_heads;
-  const bool has_kz = a.k.zeros != nullptr, has_vz = a.v.zeros != nullptr;
+  constexpr bool has_kz = ZK, has_vz = ZV;       // zero-point arrays exist unless the tensor is symmetric-only
 
   // ---- tile range of this wave
-  const long long n_tiles = (n_both + TILE - 1) / TILE;
-  const long long base_t = n_tiles / n_splits, rem_t = n_tiles % n_splits;
-  const long long s_idx = blockIdx.x;
-  const long long t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
-  const long long t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
+  const int n_tiles = (n_both + TILE - 1) / TILE;
+  const int base_t = n_tiles / n_splits, rem_t = n_tiles % n_splits;
+  const int s_idx = blockIdx.x;
+  const int t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
+  const int t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
 
   __shared__ __attribute__((aligned(16))) _Float16 qA[NH * D];          // query operand table [head][word][mfma][slot]
   __shared__ __attribute__((aligned(16))) float qsum[NH4][NG][4];       // log2e/sqrt(d) * sum of q over each key group
@@ -174,34 +174,38 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
   const uint8_t* vcodes = a.v.codes + bh * vgroups * D * (G * BITS / 8);
   const __half* vscales = a.v.scales + bh * vgroups * D;
   const __half* vzeros = has_vz ? a.v.zeros + bh * vgroups * D : nullptr;
-  const long long last_row = n_both - 1, last_group = n_both / G - 1;
+  const int last_row = n_both - 1, last_group = n_both / G - 1;
+  constexpr int ROWB = D * BITS / 8;                   // bytes of one key row
+  constexpr int GB = G * BITS / 8;                     // bytes of one channel of one value group
 
-  auto load_tile = [&](long long tile, Regs& t) {
-    long long row = tile * TILE + lane;
+  // All offsets inside one (b, hk) slab fit 32 bits; bases are wave-uniform.
+  auto load_tile = [&](int tile, Regs& t) {
+    int row = tile * TILE + lane;
     row = row > last_row ? last_row : row;
-    const u32x4* kp = reinterpret_cast<const u32x4*>(kcodes + row * (D * BITS / 8));
+    const u32x4* kp = reinterpret_cast<const u32x4*>(kcodes + (uint32_t)row * ROWB);
 #pragma unroll
     for (int i = 0; i < KC; ++i) t.kc[i] = stream_load(kp + i);
     if constexpr (NG == 4) {
-      const u32x2 s = stream_load(reinterpret_cast<const u32x2*>(kscales + row * NG));
+      const u32x2 s = stream_load(reinterpret_cast<const u32x2*>(kscales + (uint32_t)row * NG));
       t.ks[0] = s.x; t.ks[1] = s.y;
-      if (has_kz) {
-        const u32x2 z = stream_load(reinterpret_cast<const u32x2*>(kzeros + row * NG));
+      if constexpr (has_kz) {
+        const u32x2 z = stream_load(reinterpret_cast<const u32x2*>(kzeros + (uint32_t)row * NG));
         t.kz[0] = z.x; t.kz[1] = z.y;
       }
     } else {
-      t.ks[0] = stream_load(reinterpret_cast<const uint32_t*>(kscales + row * NG));
-      if (has_kz) t.kz[0] = stream_load(reinterpret_cast<const uint32_t*>(kzeros + row * NG));
+      t.ks[0] = stream_load(reinterpret_cast<const uint32_t*>(kscales + (uint32_t)row * NG));
+      if constexpr (has_kz) t.kz[0] = stream_load(reinterpret_cast<const uint32_t*>(kzeros + (uint32_t)row * NG));
     }
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
-      long long grp = tile * GPT + gi;
+      int grp = tile * GPT + gi;
       grp = grp > last_group ? last_group : grp;
-      const u32x4* vp = reinterpret_cast<const u32x4*>(vcodes + (grp * D + 2 * lane) * (G * BITS / 8));
+      const uint32_t ch = (uint32_t)grp * D + 2 * lane;
+      const u32x4* vp = reinterpret_cast<const u32x4*>(vcodes + ch * GB);
 #pragma unroll
       for (int i = 0; i < VC; ++i) t.vc[gi][i] = stream_load(vp + i);
-      t.vs[gi] = stream_load(reinterpret_cast<const uint32_t*>(vscales + grp * D + 2 * lane));
-      if (has_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + grp * D + 2 * lane));
+      t.vs[gi] = stream_load(reinterpret_cast<const uint32_t*>(vscales + ch));
+      if constexpr (has_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + ch));
     }
   };
 
@@ -217,43 +221,49 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
   const int qa_lane = (lane & 3) * D;                                   // this lane supplies head (lane & 3) to A
   const int pa_lane = (lane & 3) * TILE;
 
-  Regs cur;
-  if (t0 < t1) load_tile(t0, cur);
-  for (long long tile = t0; tile < t1; ++tile) {
-    Regs nxt;
-    if (tile + 1 < t1) load_tile(tile + 1, nxt);       // in flight while this tile is computed
-    else nxt = cur;
-
+  auto process = [&](const Regs& cur, int tile) {
     // ================= scores: lane = token (Eq. att:1 with Eq. hybrid_dequant fused) =================
+    // one MFMA chain per key group, the chains interleaved so that consecutive MFMAs are independent
+    float4_t acc[NG][NH4];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) acc[g][n] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int wd = 0; wd < WPG; ++wd) {
+      uint32_t w[NG], wsft[NG];
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int word = g * WPG + wd;
+        w[g] = cur.kc[word / 4][word % 4];
+        wsft[g] = w[g] >> F::SH;
+      }
+#pragma unroll
+      for (int m = 0; m < MPW; ++m) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const int word = g * WPG + wd;
+          const half4_t bop = operand<BITS>(w[g], wsft[g], m);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPW + m) * 4]);
+            acc[g][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[g][n], 0, 0, 0);
+          }
+        }
+      }
+    }
     float s2[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) s2[h] = 0.f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      float4_t acc[NH4];
-#pragma unroll
-      for (int n = 0; n < NH4; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int wd = 0; wd < WPG; ++wd) {
-        const int word = g * WPG + wd;
-        const uint32_t w = cur.kc[word / 4][word % 4], wsft = w >> F::SH;
-#pragma unroll
-        for (int m = 0; m < MPW; ++m) {
-          const half4_t bop = operand<BITS>(w, wsft, m);
-#pragma unroll
-          for (int n = 0; n < NH4; ++n) {
-            const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPW + m) * 4]);
-            acc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[n], 0, 0, 0);
-          }
-        }
-      }
       const uint32_t spair = cur.ks[g / 2];
       const __half sh = __ushort_as_half((unsigned short)((g & 1) ? (spair >> 16) : (spair & 0xffffu)));
       const float sc = __half2float(sh);
       const bool asym = (g & 1) ? (spair >> 31) : ((spair >> 15) & 1u);
       const float S = fabsf(sc);
       float zeff = S * (float)(-HALFCODE);
-      if (has_kz) {
+      if constexpr (has_kz) {
         const uint32_t zpair = cur.kz[g / 2];
         const float z = __half2float(__ushort_as_half((unsigned short)((g & 1) ? (zpair >> 16) : (zpair & 0xffffu))));
         zeff = asym ? z : zeff;
@@ -263,7 +273,7 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
       for (int n = 0; n < NH4; ++n) {
         const float4_t qs = *reinterpret_cast<const float4_t*>(&qsum[n][g][0]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s2[n * 4 + i] += tS * acc[n][i] + zeff * qs[i];
+        for (int i = 0; i < 4; ++i) s2[n * 4 + i] += tS * acc[g][n][i] + zeff * qs[i];
       }
     }
 
@@ -317,7 +327,7 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
       const float S0 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair & 0xffffu))));
       const float S1 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair >> 16))));
       float z0 = S0 * (float)(-HALFCODE), z1 = S1 * (float)(-HALFCODE);
-      if (has_vz) {
+      if constexpr (has_vz) {
         const uint32_t zpair = cur.vz[gi];
         z0 = ((spair >> 15) & 1u) ? __half2float(__ushort_as_half((unsigned short)(zpair & 0xffffu))) : z0;
         z1 = (spair >> 31) ? __half2float(__ushort_as_half((unsigned short)(zpair >> 16))) : z1;
@@ -334,7 +344,28 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
         }
       }
     }
-    cur = nxt;
+  };
+
+  // ---- two register buffers, ping-pong: the next tile's loads are in flight while this one is computed
+  {
+    Regs bufA, bufB;
+    const int n = t1 - t0;
+    int i = 0;
+    if (n > 0) load_tile(t0, bufA);
+    while (i + 2 < n) {
+      load_tile(t0 + i + 1, bufB);
+      process(bufA, t0 + i);
+      load_tile(t0 + i + 2, bufA);
+      process(bufB, t0 + i + 1);
+      i += 2;
+    }
+    if (n - i == 2) {
+      load_tile(t0 + i + 1, bufB);
+      process(bufA, t0 + i);
+      process(bufB, t0 + i + 1);
+    } else if (n - i == 1) {
+      process(bufA, t0 + i);
+    }
   }
 
   // ---- partial (m, l, o) of every real head
@@ -355,23 +386,34 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, long lo
   }
 }
 
-template <int BITS, int G>
-hipError_t launch_t(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream) {
+template <int BITS, int G, bool ZK, bool ZV>
+hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, hipStream_t stream) {
   const int r = a.n_q_heads / a.n_kv_heads;
   dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_inner_kernel<BITS, G, 1><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
-  else attention_inner_kernel<BITS, G, 2><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
+  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
+  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
   return hipGetLastError();
+}
+
+template <int BITS, int G>
+hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, hipStream_t stream) {
+  const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
+  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, stream);
+  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, stream);
+  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, stream);
+  return launch_z<BITS, G, false, false>(a, n_both, n_splits, stream);
 }
 
 }  // namespace
 
 bool attention_inner_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
-  return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8;
+  // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
+  return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8 && a.capacity * D <= (1LL << 31);
 }
 
-hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream) {
+hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, hipStream_t stream) {
+  const int n_both = (int)n_both_ll;
   if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, stream);
   if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, stream);
   if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, stream);
