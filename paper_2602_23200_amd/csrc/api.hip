@@ -251,8 +251,9 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   const bool fused = attention_inner_supported(a);
   if (n_both > 0 && fused) {
     // one wavefront per split; aim at two resident wavefronts per SIMD over the whole chip
+    // (the window wavefronts of the same launch take their share of the slots)
     const long long slots = (long long)compute_units() * 4 * 2;
-    long long s = slots / ((long long)c.batch * c.n_kv_heads);
+    long long s = slots / ((long long)c.batch * c.n_kv_heads) - ceil_div(win_tokens, kWindowChunk);
     const long long n_tiles = ceil_div(n_both, 64);
     if (s > n_tiles) s = n_tiles;
     if (s > split_cap(c)) s = split_cap(c);
@@ -279,12 +280,16 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   g_prof_start = g_prof_stop = nullptr;
   if (n_splits > 0) {
     if (prof_start) (void)hipEventRecord(prof_start, stream);
-    if (fused) e = launch_attention_inner(a, n_both, n_splits, stream);
-    else e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+    if (fused) {
+      const WindowSet win = {n_sink, win_b0, win_b1 - win_b0, n_win};
+      e = launch_attention_inner(a, n_both, n_splits, win, stream);
+    } else {
+      e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+    }
     if (prof_stop) (void)hipEventRecord(prof_stop, stream);
     if (e != hipSuccess) return INNERQ_E_HIP;
   }
-  if (n_win > 0) {
+  if (n_win > 0 && !(fused && n_splits > 0)) {
     e = launch_attention_generic(a, 0, n_sink, win_b0, win_b1, n_win, n_splits, stream);
     if (e != hipSuccess) return INNERQ_E_HIP;
   }

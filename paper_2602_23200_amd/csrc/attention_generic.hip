@@ -8,6 +8,7 @@
 // quantised part and the window parts are concatenated before the softmax is
 // normalised (Eq. att:1-3; Figure "quantization_overall").
 #include "innerq_dev.h"
+#include "window_pass.h"
 
 namespace innerq {
 namespace {
@@ -18,31 +19,8 @@ constexpr int TILE = 64;          // tokens per inner tile
 
 __device__ inline float h2f(__half h) { return __half2float(h); }
 
-// Element (token t, channel c) of one tensor of sequence-head bh, decoded per Eq. hybrid_dequant.
 __device__ inline float fetch(const TensorView& tv, const AttnArgs& a, long long bh, long long t, int c) {
-  if (t < tv.n_sink) return h2f(tv.sink[(bh * a.w_sink + t) * D + c]);
-  const long long row = t - a.w_sink;
-  if (row >= tv.n_quant) return h2f(tv.ring[(bh * tv.slots + (t % tv.slots)) * D + c]);
-  if (tv.form == kFp16) return h2f(reinterpret_cast<const __half*>(tv.codes)[(bh * a.capacity + row) * D + c]);
-  const int bits = a.bits, G = a.group;
-  const unsigned mask = (1u << bits) - 1u;
-  long long si;
-  unsigned field;
-  if (tv.form == kPerToken) {
-    const unsigned byte = tv.codes[((bh * a.capacity + row) * D * bits) / 8 + (c * bits) / 8];
-    field = (byte >> ((c * bits) % 8)) & mask;
-    si = (bh * a.capacity + row) * (D / G) + c / G;
-  } else {
-    const long long tg = row / G;
-    const int j = (int)(row % G);
-    si = (bh * (a.capacity / G) + tg) * D + c;
-    const unsigned byte = tv.codes[si * ((G * bits) / 8) + (j * bits) / 8];
-    field = (byte >> ((j * bits) % 8)) & mask;
-  }
-  const float s = h2f(tv.scales[si]);
-  const bool asym = __float_as_uint(s) >> 31;
-  const float S = fabsf(s);
-  return asym ? S * (float)field + h2f(tv.zeros[si]) : S * (float)((int)field - (1 << (bits - 1)));
+  return fetch_element(tv, a, bh, t, c);
 }
 
 __global__ void __launch_bounds__(256) attention_generic_kernel(AttnArgs a, long long a0, long long a1,
@@ -166,24 +144,37 @@ __global__ void __launch_bounds__(256) attention_generic_kernel(AttnArgs a, long
   }
 }
 
-// out[b][hq][:] = sum_p w_p o_p / sum_p w_p l_p,  w_p = exp(m_p - max_p m_p)
-__global__ void __launch_bounds__(D) attention_merge_kernel(AttnArgs a) {
+// out[b][hq][:] = sum_p w_p o_p / sum_p w_p l_p,  w_p = exp(m_p - max_p m_p).
+// One wavefront per query head, a lane per channel pair; the partial index is wave-uniform.
+__global__ void __launch_bounds__(64) attention_merge_kernel(AttnArgs a) {
   const long long bhq = blockIdx.x;
-  const int c = threadIdx.x;
-  const float* ml = a.ws_ml + bhq * a.n_partials * 2;
-  float M = -INFINITY;
-  for (int p = 0; p < a.n_partials; ++p) M = fmaxf(M, ml[2 * p]);
-  float num = 0.f, den = 0.f;
-  for (int p = 0; p < a.n_partials; ++p) {
+  const int lane = threadIdx.x;
+  const int P = a.n_partials;
+  const float* ml = a.ws_ml + bhq * P * 2;
+  const float* po = a.ws_o + bhq * P * D + 2 * lane;
+  float mloc = -INFINITY;
+  for (int p = lane; p < P; p += 64) mloc = fmaxf(mloc, ml[2 * p]);
+  const float M = window_wave_max(mloc);
+  float n0 = 0.f, n1 = 0.f, den = 0.f;
+#pragma unroll 4
+  for (int p = 0; p < P; ++p) {
     const float m = ml[2 * p];
-    if (m == -INFINITY) continue;                        // empty partial
-    const float w = expf(m - M);
+    const float w = m == -INFINITY ? 0.f : __expf(m - M);        // an empty partial has m = -inf
+    const float2 ov = *reinterpret_cast<const float2*>(po + (long long)p * D);
     den += w * ml[2 * p + 1];
-    num += w * a.ws_o[(bhq * a.n_partials + p) * D + c];
+    n0 += w * ov.x;
+    n1 += w * ov.y;
   }
-  const float r = num / den;
-  if (a.out_is_fp32) reinterpret_cast<float*>(a.out)[bhq * D + c] = r;
-  else reinterpret_cast<__half*>(a.out)[bhq * D + c] = __float2half_rn(r);
+  const float inv = 1.0f / den;
+  if (a.out_is_fp32) {
+    float2 r;
+    r.x = n0 * inv;
+    r.y = n1 * inv;
+    *reinterpret_cast<float2*>(reinterpret_cast<float*>(a.out) + bhq * D + 2 * lane) = r;
+  } else {
+    __half2 r = __floats2half2_rn(n0 * inv, n1 * inv);
+    *reinterpret_cast<__half2*>(reinterpret_cast<__half*>(a.out) + bhq * D + 2 * lane) = r;
+  }
 }
 
 }  // namespace
@@ -197,7 +188,7 @@ hipError_t launch_attention_generic(const AttnArgs& a, long long a0, long long a
 }
 
 hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream) {
-  attention_merge_kernel<<<(unsigned)(a.batch * a.n_q_heads), D, 0, stream>>>(a);
+  attention_merge_kernel<<<(unsigned)(a.batch * a.n_q_heads), 64, 0, stream>>>(a);
   return hipGetLastError();
 }
 

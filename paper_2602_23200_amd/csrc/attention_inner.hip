@@ -28,6 +28,7 @@
 //     normaliser is the MFMA sum of those same rounded values (an extra all-ones B
 //     operand), so the weights stay consistent.
 #include "innerq_dev.h"
+#include "window_pass.h"
 
 namespace innerq {
 namespace {
@@ -111,7 +112,7 @@ struct TileRegs {
 };
 
 template <int BITS, int G, int NH4, bool ZK, bool ZV>
-__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_both, int n_splits) {
+__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   using F = Fields<BITS>;
   using Regs = TileRegs<BITS, G>;
   constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC;
@@ -128,10 +129,15 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
   const int r = a.n_q_heads / a.n_kv_heads;
   constexpr bool has_kz = ZK, has_vz = ZV;       // zero-point arrays exist unless the tensor is symmetric-only
 
+  if ((int)blockIdx.x < win.n_chunks) {               // the first wavefronts serve the fp16 windows instead
+    window_pass<NH4>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
+    return;
+  }
+
   // ---- tile range of this wave
   const int n_tiles = (n_both + TILE - 1) / TILE;
   const int base_t = n_tiles / n_splits, rem_t = n_tiles % n_splits;
-  const int s_idx = blockIdx.x;
+  const int s_idx = (int)blockIdx.x - win.n_chunks;
   const int t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
   const int t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
 
@@ -369,7 +375,7 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
   }
 
   // ---- partial (m, l, o) of every real head
-  const int slot = blockIdx.x;
+  const int slot = s_idx;
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
     if (h < r) {
@@ -387,21 +393,21 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
 }
 
 template <int BITS, int G, bool ZK, bool ZV>
-hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, hipStream_t stream) {
+hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
   const int r = a.n_q_heads / a.n_kv_heads;
-  dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
-  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits);
+  dim3 grid((unsigned)(n_splits + win.n_chunks), (unsigned)(a.batch * a.n_kv_heads));
+  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
+  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
   return hipGetLastError();
 }
 
 template <int BITS, int G>
-hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, hipStream_t stream) {
+hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
   const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, stream);
-  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, stream);
-  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, stream);
-  return launch_z<BITS, G, false, false>(a, n_both, n_splits, stream);
+  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, stream);
+  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, stream);
+  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, stream);
+  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, stream);
 }
 
 }  // namespace
@@ -412,12 +418,13 @@ bool attention_inner_supported(const AttnArgs& a) {
   return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8 && a.capacity * D <= (1LL << 31);
 }
 
-hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, hipStream_t stream) {
+hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
+                                  hipStream_t stream) {
   const int n_both = (int)n_both_ll;
-  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, stream);
-  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, stream);
-  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, stream);
-  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, stream);
+  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, stream);
+  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, stream);
+  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, stream);
+  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, stream);
   return hipErrorInvalidValue;
 }
 

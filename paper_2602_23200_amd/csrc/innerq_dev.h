@@ -11,7 +11,7 @@
 namespace innerq {
 
 constexpr int kHeadDim = 128;          // the only head_dim built
-constexpr int kWindowChunk = 256;      // tokens per work-group of the generic (window) kernel
+constexpr int kWindowChunk = 64;       // window tokens per wavefront / work-group chunk
 constexpr int kHeadTile = 4;           // query heads served by one work-group pass
 
 enum Form : int { kPerToken = 0, kPerChannel = 1, kFp16 = 2 };
@@ -97,7 +97,11 @@ hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
 
 // Fused MFMA kernel for the inner-grouped layout: tokens [w_sink, w_sink + n_both) cut into
 // n_splits contiguous ranges of 64-token tiles, one wavefront each, partial slots 0 .. n_splits.
+// The same launch carries win.n_chunks extra wavefronts per (batch, kv-head) that serve the
+// window token set [0, na) U [b0, b0 + nb) (partial slots n_splits .. n_splits + n_chunks).
+struct WindowSet { long long na, b0, nb; int n_chunks; };
 bool attention_inner_supported(const AttnArgs& a);
-hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, hipStream_t stream);
+hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
+                                  hipStream_t stream);
 
 }  // namespace innerq
