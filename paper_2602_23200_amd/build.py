@@ -17,7 +17,8 @@ SOURCES = {
     "api.hip": [],
     "quantize.hip": ["-ffp-contract=off"],
     "attention_generic.hip": [],
-    "attention_inner.hip": ["-save-temps=obj"] if os.environ.get("INNERQ_SAVE_TEMPS") else [],
+    # no NaN canonicalisation around fmax; MFMA results straight into VGPRs
+    "attention_inner.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -215,10 +215,16 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
     }
   };
 
-  // ---- running softmax state (log2 domain) and output accumulators
+  // ---- running softmax state (log2 domain) and output accumulators.
+  // m_run is a reference level, not the exact running maximum: it is raised (and l, o rescaled)
+  // only when some score exceeds it by more than kSlack, so the common tile pays no wave-wide
+  // reduction and no rescale.  Probabilities are then at most 2^kSlack, times the position
+  // factor 2^8: still inside fp16.  l_run and o are kept divided by 2^16 (the raw MFMA scale).
+  // The first tile sets the level to its exact maximum.
+  constexpr float kSlack = 6.0f;
   float m_run[NH], l_run[NH], o[NH][2];
 #pragma unroll
-  for (int h = 0; h < NH; ++h) { m_run[h] = -INFINITY; l_run[h] = 0.f; o[h][0] = 0.f; o[h][1] = 0.f; }
+  for (int h = 0; h < NH; ++h) { m_run[h] = 0.f; l_run[h] = 0.f; o[h][0] = 0.f; o[h][1] = 0.f; }
 
   // where this lane's token sits in the probability operand table, and its position factor
   const int p_e = lane % F::FPW;
@@ -258,9 +264,10 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
         }
       }
     }
-    float s2[NH];
+    // e[h] = score (log2 domain) + position shift - reference level: the exponent of the stored probability
+    float e[NH];
 #pragma unroll
-    for (int h = 0; h < NH; ++h) s2[h] = 0.f;
+    for (int h = 0; h < NH; ++h) e[h] = p_shift - m_run[h];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       const uint32_t spair = cur.ks[g / 2];
@@ -279,25 +286,37 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
       for (int n = 0; n < NH4; ++n) {
         const float4_t qs = *reinterpret_cast<const float4_t*>(&qsum[n][g][0]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s2[n * 4 + i] += tS * acc[g][n][i] + zeff * qs[i];
+        for (int i = 0; i < 4; ++i)
+          e[n * 4 + i] = __builtin_fmaf(tS, acc[g][n][i], __builtin_fmaf(zeff, qs[i], e[n * 4 + i]));
       }
     }
 
     // ================= running softmax (Eq. att:2), probabilities to the operand table =================
-    const bool valid = tile * TILE + lane <= last_row;
+    if (tile * TILE + (TILE - 1) > last_row) {         // ragged last tile: lanes past the end weigh nothing
+      const bool valid = tile * TILE + lane <= last_row;
+#pragma unroll
+      for (int h = 0; h < NH; ++h) e[h] = valid ? e[h] : -INFINITY;
+    }
+    const bool first = tile == t0;
+    bool raise = false;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) raise |= e[h] > kSlack + p_shift;
+    if (first || __builtin_amdgcn_ballot_w64(raise) != 0) {   // rare after the first tiles
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const float mx = wave_max(e[h] - p_shift);           // largest score relative to the current level
+        const float d = first ? mx : fmaxf(mx, 0.f);         // the level only rises, except when it is first set
+        const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-d);
+        m_run[h] += d;
+        e[h] -= d;
+        l_run[h] *= alpha;
+        o[h][0] *= alpha;
+        o[h][1] *= alpha;
+      }
+    }
     __syncthreads();                                   // previous tile's readers of pA are done
 #pragma unroll
-    for (int h = 0; h < NH; ++h) {
-      const float sv = valid ? s2[h] : -INFINITY;
-      const float m_new = fmaxf(m_run[h], wave_max(sv));
-      const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);
-      m_run[h] = m_new;
-      l_run[h] *= alpha;
-      o[h][0] *= alpha;
-      o[h][1] *= alpha;
-      const float p = __builtin_amdgcn_exp2f(sv - m_new + p_shift);
-      pA[h * TILE + p_index] = (_Float16)p;
-    }
+    for (int h = 0; h < NH; ++h) pA[h * TILE + p_index] = (_Float16)__builtin_amdgcn_exp2f(e[h]);
     __syncthreads();
 
     // ================= values: lane = two channels (Eq. att:3 with Eq. hybrid_dequant fused) =================
@@ -338,15 +357,14 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
         z0 = ((spair >> 15) & 1u) ? __half2float(__ushort_as_half((unsigned short)(zpair & 0xffffu))) : z0;
         z1 = (spair >> 31) ? __half2float(__ushort_as_half((unsigned short)(zpair >> 16))) : z1;
       }
-      const float tS0 = S0 * 65536.0f, tS1 = S1 * 65536.0f;             // 2^16 undoes the operand factors
+      // accl = 2^-16 * (sum of the fp16 probabilities of this group); l and o stay in that scale
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float psum = accl[n][i] * 65536.0f;                     // sum of the fp16 probabilities of this group
-          l_run[n * 4 + i] += psum;
-          o[n * 4 + i][0] += tS0 * acc0[n][i] + z0 * psum;
-          o[n * 4 + i][1] += tS1 * acc1[n][i] + z1 * psum;
+          l_run[n * 4 + i] += accl[n][i];
+          o[n * 4 + i][0] = __builtin_fmaf(S0, acc0[n][i], __builtin_fmaf(z0, accl[n][i], o[n * 4 + i][0]));
+          o[n * 4 + i][1] = __builtin_fmaf(S1, acc1[n][i], __builtin_fmaf(z1, accl[n][i], o[n * 4 + i][1]));
         }
       }
     }
@@ -381,12 +399,12 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
     if (h < r) {
       const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
       float2 ov;
-      ov.x = o[h][0];
-      ov.y = o[h][1];
+      ov.x = o[h][0] * 65536.0f;                       // 2^16 undoes the operand factors of the value pass
+      ov.y = o[h][1] * 65536.0f;
       *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + slot) * D + 2 * lane]) = ov;
       if (lane == 0) {
         a.ws_ml[(bhq * a.n_partials + slot) * 2 + 0] = m_run[h] * kLn2;
-        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h];
+        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h] * 65536.0f;
       }
     }
   }
