@@ -250,9 +250,9 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   int n_splits = 0;
   const bool fused = attention_inner_supported(a);
   if (n_both > 0 && fused) {
-    // one wavefront per split; aim at two resident wavefronts per SIMD over the whole chip
+    // one wavefront per split; every wavefront of the launch resident at once, no tail round
     // (the window wavefronts of the same launch take their share of the slots)
-    const long long slots = (long long)compute_units() * 4 * 2;
+    const long long slots = (long long)compute_units() * attention_inner_waves_per_cu(a);
     long long s = slots / ((long long)c.batch * c.n_kv_heads) - ceil_div(win_tokens, kWindowChunk);
     const long long n_tiles = ceil_div(n_both, 64);
     if (s > n_tiles) s = n_tiles;

@@ -410,6 +410,7 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
   }
 }
 
+// op = 0: launch; op = 1: return (as an int cast to hipError_t's slot) nothing -- see resident_waves_z
 template <int BITS, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
   const int r = a.n_q_heads / a.n_kv_heads;
@@ -417,6 +418,17 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
   else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
   return hipGetLastError();
+}
+
+// Wavefronts of this kernel instance that one compute unit holds at once (a host-side query).
+template <int BITS, int G, bool ZK, bool ZV>
+int resident_z(const AttnArgs& a) {
+  const int r = a.n_q_heads / a.n_kv_heads;
+  int n = 0;
+  hipError_t e = r <= 4
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<BITS, G, 1, ZK, ZV>, 64, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<BITS, G, 2, ZK, ZV>, 64, 0);
+  return (e == hipSuccess && n > 0) ? n : 8;
 }
 
 template <int BITS, int G>
@@ -428,12 +440,35 @@ hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, stream);
 }
 
+template <int BITS, int G>
+int resident_t(const AttnArgs& a) {
+  const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
+  if (zk && zv) return resident_z<BITS, G, true, true>(a);
+  if (zk) return resident_z<BITS, G, true, false>(a);
+  if (zv) return resident_z<BITS, G, false, true>(a);
+  return resident_z<BITS, G, false, false>(a);
+}
+
 }  // namespace
 
 bool attention_inner_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
   return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8 && a.capacity * D <= (1LL << 31);
+}
+
+int attention_inner_waves_per_cu(const AttnArgs& a) {
+  // cached per (bits, group, zero flags, head tile): the answer depends on the kernel instance only
+  static int cache[2][2][2][2][2] = {};
+  const int r = a.n_q_heads / a.n_kv_heads;
+  int& c = cache[a.bits == 4][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
+  if (c == 0) {
+    if (a.bits == 2 && a.group == 32) c = resident_t<2, 32>(a);
+    else if (a.bits == 2 && a.group == 64) c = resident_t<2, 64>(a);
+    else if (a.bits == 4 && a.group == 32) c = resident_t<4, 32>(a);
+    else c = resident_t<4, 64>(a);
+  }
+  return c;
 }
 
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,

@@ -101,6 +101,7 @@ hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
 // window token set [0, na) U [b0, b0 + nb) (partial slots n_splits .. n_splits + n_chunks).
 struct WindowSet { long long na, b0, nb; int n_chunks; };
 bool attention_inner_supported(const AttnArgs& a);
+int attention_inner_waves_per_cu(const AttnArgs& a);   // resident wavefronts per compute unit
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                   hipStream_t stream);
 
