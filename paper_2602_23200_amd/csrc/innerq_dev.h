@@ -105,4 +105,10 @@ int attention_inner_waves_per_cu(const AttnArgs& a);   // resident wavefronts pe
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                   hipStream_t stream);
 
+// Comparison kernel over an unquantised fp16 store, same launch shape.
+bool attention_fp16_supported(const AttnArgs& a);
+int attention_fp16_waves_per_cu(const AttnArgs& a);
+hipError_t launch_attention_fp16(const AttnArgs& a, long long n_rows, int n_splits, const WindowSet& win,
+                                 hipStream_t stream);
+
 }  // namespace innerq
