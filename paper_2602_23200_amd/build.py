@@ -18,6 +18,7 @@ SOURCES = {
     "quantize.hip": ["-ffp-contract=off"],
     "attention_generic.hip": [],
     "attention_fp16.hip": ["-fno-honor-nans"],
+    "attention_outer.hip": ["-fno-honor-nans"],
     # no NaN canonicalisation around fmax; MFMA results straight into VGPRs
     "attention_inner.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
 }

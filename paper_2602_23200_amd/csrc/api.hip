@@ -249,13 +249,16 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   const int r = c.n_q_heads / c.n_kv_heads;
   int n_splits = 0;
   // which fused kernel serves this cache (0 = none: element-by-element fallback)
-  const int fused_kind = attention_inner_supported(a) ? 1 : attention_fp16_supported(a) ? 2 : 0;
+  const int fused_kind =
+      attention_inner_supported(a) ? 1 : attention_fp16_supported(a) ? 2 : attention_outer_supported(a) ? 3 : 0;
   const bool fused = fused_kind != 0;
   if (n_both > 0 && fused) {
     // one wavefront per split; every wavefront of the launch resident at once, no tail round
     // (the window wavefronts of the same launch take their share of the slots)
     const long long slots = (long long)compute_units() *
-                            (fused_kind == 1 ? attention_inner_waves_per_cu(a) : attention_fp16_waves_per_cu(a));
+                            (fused_kind == 1   ? attention_inner_waves_per_cu(a)
+                             : fused_kind == 2 ? attention_fp16_waves_per_cu(a)
+                                               : attention_outer_waves_per_cu(a));
     long long s = slots / ((long long)c.batch * c.n_kv_heads) - ceil_div(win_tokens, kWindowChunk);
     const long long n_tiles = ceil_div(n_both, 64);
     if (s > n_tiles) s = n_tiles;
@@ -285,8 +288,9 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
     if (prof_start) (void)hipEventRecord(prof_start, stream);
     if (fused) {
       const WindowSet win = {n_sink, win_b0, win_b1 - win_b0, n_win};
-      e = fused_kind == 1 ? launch_attention_inner(a, n_both, n_splits, win, stream)
-                          : launch_attention_fp16(a, n_both, n_splits, win, stream);
+      e = fused_kind == 1   ? launch_attention_inner(a, n_both, n_splits, win, stream)
+          : fused_kind == 2 ? launch_attention_fp16(a, n_both, n_splits, win, stream)
+                            : launch_attention_outer(a, n_both, n_splits, win, stream);
     } else {
       e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
     }

@@ -111,4 +111,10 @@ int attention_fp16_waves_per_cu(const AttnArgs& a);
 hipError_t launch_attention_fp16(const AttnArgs& a, long long n_rows, int n_splits, const WindowSet& win,
                                  hipStream_t stream);
 
+// Comparison kernel over an outer-grouped cache, same launch shape.
+bool attention_outer_supported(const AttnArgs& a);
+int attention_outer_waves_per_cu(const AttnArgs& a);
+hipError_t launch_attention_outer(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
+                                  hipStream_t stream);
+
 }  // namespace innerq
