@@ -49,8 +49,10 @@
  *   asymmetric group and +0 otherwise.  Decoding is Eq. hybrid_dequant:
  *   x^ = |scale| * code + M * zero.
  *   Windows: k_sink, v_sink fp16 [B][Hk][w_sink][d];
- *   k_recent, v_recent fp16 [B][Hk][slots][d], slots = w_recent for a per-token
- *   or fp16 tensor and w_recent + G for a per-channel tensor.
+ *   k_recent, v_recent fp16 [B][Hk][slots][d], slots = w_recent + 1 for a per-token
+ *   or fp16 tensor and w_recent + G for a per-channel tensor (the window itself holds
+ *   w_recent, resp. up to w_recent + G - 1, tokens; the spare slot lets a decode step
+ *   write the new token without waiting for the evicted one to be read).
  */
 #ifndef INNERQ_H
 #define INNERQ_H

@@ -80,7 +80,9 @@ class Config:
         return self.k_mode if which == "k" else self.v_mode
 
     def ring_slots(self, which: str) -> int:
-        extra = self.group if self.form(which) == FORM_PER_CHANNEL else 0
+        # the recent window holds w_recent tokens (up to w_recent + G - 1 for a tensor grouped
+        # along tokens); the buffer has one spare slot (G spare slots) beyond that
+        extra = self.group if self.form(which) == FORM_PER_CHANNEL else 1
         return self.w_recent + extra
 
 

@@ -50,7 +50,9 @@ inline Partition partition_of(const innerq_config_t& c, int which, long long n) 
 }
 
 inline int ring_slots(const innerq_config_t& c, int which) {
-  return c.w_recent + (form_of(c.kind, which) == kPerChannel ? c.group : 0);
+  // one spare slot (or G of them) beyond the window: the newest token never has to land in the
+  // slot of a token that is evicted in the same step
+  return c.w_recent + (form_of(c.kind, which) == kPerChannel ? c.group : 1);
 }
 
 // ---- launchers implemented in the kernel translation units --------------------------------

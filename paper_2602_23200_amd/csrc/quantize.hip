@@ -68,13 +68,48 @@ __device__ inline const __half* token_row(const QuantTensorJob& j, const QuantAr
   return j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
 }
 
+// New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
+// ring -- unless this same call already moved them on to the quantised store.
+__device__ inline void window_copy(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
+  constexpr int CPR = kHeadDim / 8;
+  const long long BH = (long long)a.batch * a.n_kv_heads;
+  if (idx >= BH * a.t_new * CPR) return;
+  const int ch = (int)(idx % CPR);
+  const long long i = (idx / CPR) % a.t_new;
+  const long long bh = idx / (CPR * a.t_new);
+  const long long t = a.n_old + i;
+  __half* dst;
+  if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
+  else if (t >= j.ring_from) dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
+  else return;
+  uint4 raw = *reinterpret_cast<const uint4*>(j.x_new + (bh * a.t_new + i) * kHeadDim + ch * 8);
+  if (j.normalise) {
+    __half* h = reinterpret_cast<__half*>(&raw);
+    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
+  }
+  *reinterpret_cast<uint4*>(dst + ch * 8) = raw;
+}
+
+__global__ void __launch_bounds__(256) window_copy_kernel(QuantArgs a) {
+  window_copy(a, a.job[blockIdx.y], (long long)blockIdx.x * blockDim.x + threadIdx.x);
+}
+
 template <int G, int BITS>
-__global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a) {
+__global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long copy_from) {
+  // Thread indices below copy_from quantise evicted tokens, those from copy_from on write the
+  // new tokens into the windows (one launch; only used when no new token lands in a ring slot
+  // that this call still has to read).  copy_from < 0: no copy work in this launch.
   const QuantTensorJob& j = a.job[blockIdx.y];
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (copy_from >= 0 && idx >= copy_from) {
+    window_copy(a, j, idx - copy_from);
+    return;
+  }
   const long long n_rows = j.row_end - j.row_begin;
   if (n_rows <= 0) return;
   const long long BH = (long long)a.batch * a.n_kv_heads;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   constexpr int W = G * BITS / 32;
 
   if (j.form == kPerToken) {
@@ -152,32 +187,6 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a) {
   }
 }
 
-// New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
-// ring -- unless this same call already moved them on to the quantised store.
-__global__ void __launch_bounds__(256) window_copy_kernel(QuantArgs a) {
-  const QuantTensorJob& j = a.job[blockIdx.y];
-  constexpr int CPR = kHeadDim / 8;
-  const long long BH = (long long)a.batch * a.n_kv_heads;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= BH * a.t_new * CPR) return;
-  const int ch = (int)(idx % CPR);
-  const long long i = (idx / CPR) % a.t_new;
-  const long long bh = idx / (CPR * a.t_new);
-  const long long t = a.n_old + i;
-  __half* dst;
-  if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
-  else if (t >= j.ring_from) dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
-  else return;
-  uint4 raw = *reinterpret_cast<const uint4*>(j.x_new + (bh * a.t_new + i) * kHeadDim + ch * 8);
-  if (j.normalise) {
-    __half* h = reinterpret_cast<__half*>(&raw);
-    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
-  }
-  *reinterpret_cast<uint4*>(dst + ch * 8) = raw;
-}
-
 template <int G, int BITS>
 hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
   const long long BH = (long long)a.batch * a.n_kv_heads;
@@ -192,13 +201,29 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
     else n = BH * rows * (kHeadDim / 8);
     threads = n > threads ? n : threads;
   }
+  const long long cthreads = BH * a.t_new * (kHeadDim / 8);
+  // A new token may overwrite a ring slot only after the old token in it has been read.  If
+  // every token from the oldest one evicted in this call to the newest one appended fits the
+  // ring at once, no slot is shared and one launch does both jobs.
+  bool disjoint = true;
+  for (int w = 0; w < 2; ++w) {
+    const QuantTensorJob& j = a.job[w];
+    if (j.row_end > j.row_begin && a.w_sink + j.row_begin < a.n_old &&
+        a.n_old + a.t_new - (a.w_sink + j.row_begin) > j.slots)
+      disjoint = false;
+  }
+  if (threads > 0 && disjoint) {
+    const long long qthreads = ((threads + 255) / 256) * 256;
+    dim3 grid((unsigned)((qthreads + cthreads + 255) / 256), 2);
+    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a, qthreads);
+    return hipGetLastError();
+  }
   if (threads > 0) {
     dim3 grid((unsigned)((threads + 255) / 256), 2);
-    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a);
+    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a, -1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const long long cthreads = BH * a.t_new * (kHeadDim / 8);
   dim3 grid((unsigned)((cthreads + 255) / 256), 2);
   window_copy_kernel<<<grid, 256, 0, stream>>>(a);
   return hipGetLastError();
