@@ -11,15 +11,18 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 
 inline long long ceil_div(long long a, long long b) { return (a + b - 1) / b; }
 
-// Most token splits a launch may use for the quantised range; bounds the workspace.
+inline int window_chunk_cap(const innerq_config_t& c) {
+  return (int)ceil_div((long long)c.w_sink + c.w_recent + 2LL * c.group, kWindowChunk) + 1;
+}
+// Most token splits a launch may use for the quantised range; bounds the workspace.  Never below
+// the window chunk count plus one: the fused inner kernel needs one wavefront beyond those that
+// carry a window chunk.
 inline int split_cap(const innerq_config_t& c) {
   long long s = ceil_div(4096, (long long)c.batch * c.n_kv_heads);
   if (s < 4) s = 4;
   if (s > 512) s = 512;
+  if (s < window_chunk_cap(c) + 1) s = window_chunk_cap(c) + 1;
   return (int)s;
-}
-inline int window_chunk_cap(const innerq_config_t& c) {
-  return (int)ceil_div((long long)c.w_sink + c.w_recent + 2LL * c.group, kWindowChunk) + 1;
 }
 
 int check_config(const innerq_config_t* c) {
@@ -259,11 +262,21 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
                             (fused_kind == 1   ? attention_inner_waves_per_cu(a)
                              : fused_kind == 2 ? attention_fp16_waves_per_cu(a)
                                                : attention_outer_waves_per_cu(a));
-    long long s = slots / ((long long)c.batch * c.n_kv_heads) - ceil_div(win_tokens, kWindowChunk);
+    const long long n_win_chunks = ceil_div(win_tokens, kWindowChunk);
     const long long n_tiles = ceil_div(n_both, 64);
-    if (s > n_tiles) s = n_tiles;
-    if (s > split_cap(c)) s = split_cap(c);
-    if (s < 1) s = 1;
+    long long s = slots / ((long long)c.batch * c.n_kv_heads);
+    if (fused_kind == 1) {
+      // the inner kernel's first wavefronts each carry a window chunk besides their tiles
+      if (s > n_tiles + n_win_chunks) s = n_tiles + n_win_chunks;
+      if (s > split_cap(c)) s = split_cap(c);
+      if (s < n_win_chunks + 1) s = n_win_chunks + 1;
+    } else {
+      // the comparison kernels run the window chunks as extra wavefronts of the same launch
+      s -= n_win_chunks;
+      if (s > n_tiles) s = n_tiles;
+      if (s > split_cap(c)) s = split_cap(c);
+      if (s < 1) s = 1;
+    }
     n_splits = (int)s;
   } else if (n_both > 0) {
     const long long blocks_per_split = (long long)c.batch * c.n_kv_heads * ceil_div(r, kHeadTile);

@@ -39,7 +39,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int r = a.n_q_heads / a.n_kv_heads;
 
   if ((int)blockIdx.x < win.n_chunks) {
-    window_pass<NH4>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
+    window_pass<NH4, 4, 32, false, false>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
     return;
   }
   const int n_tiles = (n_rows + TILE - 1) / TILE;

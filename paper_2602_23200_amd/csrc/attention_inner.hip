@@ -27,6 +27,8 @@
 //   * softmax probabilities are rounded to fp16 for the value pass and the
 //     normaliser is the MFMA sum of those same rounded values (an extra all-ones B
 //     operand), so the weights stay consistent.
+#include <stdlib.h>
+
 #include "innerq_dev.h"
 #include "window_pass.h"
 
@@ -112,7 +114,7 @@ struct TileRegs {
 };
 
 template <int BITS, int G, int NH4, bool ZK, bool ZV>
-__global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles) {
   using F = Fields<BITS>;
   using Regs = TileRegs<BITS, G>;
   constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC;
@@ -129,48 +131,25 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
   const int r = a.n_q_heads / a.n_kv_heads;
   constexpr bool has_kz = ZK, has_vz = ZV;       // zero-point arrays exist unless the tensor is symmetric-only
 
-  if ((int)blockIdx.x < win.n_chunks) {               // the first wavefronts serve the fp16 windows instead
-    window_pass<NH4>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
-    return;
-  }
-
-  // ---- tile range of this wave
+  // ---- tile range of this wavefront.  The first win.n_chunks wavefronts of a (batch, kv-head)
+  // also serve one chunk of the fp16 windows each (after their tiles) and get win_tiles tiles;
+  // the others share the remaining tiles evenly.
   const int n_tiles = (n_both + TILE - 1) / TILE;
-  const int base_t = n_tiles / n_splits, rem_t = n_tiles % n_splits;
-  const int s_idx = (int)blockIdx.x - win.n_chunks;
-  const int t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
-  const int t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
+  const int s_idx = (int)blockIdx.x;
+  int t0, t1;
+  if (s_idx < win.n_chunks) {
+    t0 = s_idx * win_tiles;
+    t1 = t0 + win_tiles;
+  } else {
+    const int rest = n_tiles - win.n_chunks * win_tiles, others = n_splits - win.n_chunks, j = s_idx - win.n_chunks;
+    const int base_t = rest / others, rem_t = rest % others;
+    t0 = win.n_chunks * win_tiles + j * base_t + (j < rem_t ? j : rem_t);
+    t1 = t0 + base_t + (j < rem_t ? 1 : 0);
+  }
 
   __shared__ __attribute__((aligned(16))) _Float16 qA[NH * D];          // query operand table [head][word][mfma][slot]
   __shared__ __attribute__((aligned(16))) float qsum[NH4][NG][4];       // log2e/sqrt(d) * sum of q over each key group
   __shared__ __attribute__((aligned(16))) _Float16 pA[NH * TILE];       // probability operand table [head][word][mfma][slot]
-
-  // ---- query: fp16 (optionally rescaled), position factors folded in
-  for (int i = lane; i < NH * D; i += 64) {
-    const int h = i / D, c = i % D;
-    float qv = 0.f;
-    if (h < r) {
-      const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h) * D + c];
-      qv = a.q_scale ? __half2float(__float2half_rn(__half2float(qh) * a.q_scale[hk * D + c])) : __half2float(qh);
-    }
-    const int word = c / F::FPW, e = c % F::FPW;
-    const int f = e % F::HALF;
-    const float factor = (float)(1 << (4 + BITS * 4)) / (float)(1 << (BITS * F::pos(f) + BITS * 4));   // 2^(4 - b*pos)
-    qA[(h * NW + word) * (MPW * 4) + F::slot(e)] = (_Float16)(qv * factor);
-  }
-  __syncthreads();
-  if (lane < NH * NG) {
-    const int h = lane / NG, g = lane % NG;
-    // sum of the (rescaled) query over the group, undoing the position factors
-    float s = 0.f;
-    for (int c = g * G; c < (g + 1) * G; ++c) {
-      const int word = c / F::FPW, e = c % F::FPW, f = e % F::HALF;
-      const float factor = (float)(1 << (BITS * F::pos(f) + BITS * 4)) / (float)(1 << (4 + BITS * 4));
-      s += (float)qA[(h * NW + word) * (MPW * 4) + F::slot(e)] * factor;
-    }
-    qsum[h / 4][g][h % 4] = s * (kSmScale * kLog2e);
-  }
-  __syncthreads();
 
   // ---- per-(b, hk) base pointers
   const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * BITS / 8);
@@ -215,6 +194,48 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
     }
   };
 
+  // ---- the query loads go out first (the set-up below waits for them), the first tile's loads
+  // right behind them: those overlap the query set-up
+  u32x4 q_raw[NH4];
+#pragma unroll
+  for (int rnd = 0; rnd < NH4; ++rnd) {
+    const int h = (rnd * 64 + lane) / (D / 8), c0 = 8 * ((rnd * 64 + lane) % (D / 8));
+    q_raw[rnd] = u32x4{0u, 0u, 0u, 0u};
+    if (h < r) q_raw[rnd] = *reinterpret_cast<const u32x4*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + c0);
+  }
+  Regs bufA, bufB;
+  if (t1 > t0) load_tile(t0, bufA);
+
+  // ---- query: fp16 (optionally rescaled), position factors folded in.  A lane takes 8
+  // consecutive channels of one head (one 16-byte load); the channels of one key group sit in
+  // G/8 neighbouring lanes, so the group sums of q come from a few DPP adds.
+#pragma unroll
+  for (int rnd = 0; rnd < NH4; ++rnd) {
+    const int idx = rnd * 64 + lane;
+    const int h = idx / (D / 8), c0 = 8 * (idx % (D / 8));
+    const uint32_t rw[4] = {q_raw[rnd].x, q_raw[rnd].y, q_raw[rnd].z, q_raw[rnd].w};
+    float part = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t hb = (e & 1) ? (rw[e / 2] >> 16) : (rw[e / 2] & 0xffffu);
+      float qv = __half2float(__ushort_as_half((unsigned short)hb));
+      if (a.q_scale) qv = __half2float(__float2half_rn(qv * a.q_scale[hk * D + c0 + e]));
+      part += qv;
+      const int c = c0 + e;
+      const int word = c / F::FPW, ep = c % F::FPW;
+      const int f = ep % F::HALF;
+      const float factor = (float)(1 << (4 + BITS * 4)) / (float)(1 << (BITS * F::pos(f) + BITS * 4));   // 2^(4 - b*pos)
+      qA[(h * NW + word) * (MPW * 4) + F::slot(ep)] = (_Float16)(qv * factor);
+    }
+    // sum over the G/8 lanes of the group (4 lanes: one quad; 8 lanes: two quads)
+    part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0xB1, 0xF, 0xF, true));
+    part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0x4E, 0xF, 0xF, true));
+    if constexpr (G == 64)
+      part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0x141, 0xF, 0xF, true));
+    if ((idx % (G / 8)) == 0) qsum[h / 4][c0 / G][h % 4] = part * (kSmScale * kLog2e);
+  }
+  __syncthreads();
+
   // ---- running softmax state (log2 domain) and output accumulators.
   // m_run is a reference level, not the exact running maximum: it is raised (and l, o rescaled)
   // only when some score exceeds it by more than kSlack, so the common tile pays no wave-wide
@@ -233,7 +254,7 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
   const int qa_lane = (lane & 3) * D;                                   // this lane supplies head (lane & 3) to A
   const int pa_lane = (lane & 3) * TILE;
 
-  auto process = [&](const Regs& cur, int tile) {
+  auto process = [&](const Regs& cur, int tile, bool first) {
     // ================= scores: lane = token (Eq. att:1 with Eq. hybrid_dequant fused) =================
     // one MFMA chain per key group, the chains interleaved so that consecutive MFMAs are independent
     float4_t acc[NG][NH4];
@@ -297,7 +318,6 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
 #pragma unroll
       for (int h = 0; h < NH; ++h) e[h] = valid ? e[h] : -INFINITY;
     }
-    const bool first = tile == t0;
     bool raise = false;
 #pragma unroll
     for (int h = 0; h < NH; ++h) raise |= e[h] > kSlack + p_shift;
@@ -372,23 +392,31 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
 
   // ---- two register buffers, ping-pong: the next tile's loads are in flight while this one is computed
   {
-    Regs bufA, bufB;
     const int n = t1 - t0;
     int i = 0;
-    if (n > 0) load_tile(t0, bufA);
     while (i + 2 < n) {
+      // the wavefront that is behind gets the SIMD first: the two wavefronts of a SIMD then
+      // finish together instead of one running alone (and at a lower rate) at the end
+      if (4 * i < n) __builtin_amdgcn_s_setprio(3);
+      else if (2 * i < n) __builtin_amdgcn_s_setprio(2);
+      else if (4 * i < 3 * n) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
       load_tile(t0 + i + 1, bufB);
-      process(bufA, t0 + i);
+      process(bufA, t0 + i, i == 0);
       load_tile(t0 + i + 2, bufA);
-      process(bufB, t0 + i + 1);
+      process(bufB, t0 + i + 1, false);
       i += 2;
     }
     if (n - i == 2) {
       load_tile(t0 + i + 1, bufB);
-      process(bufA, t0 + i);
-      process(bufB, t0 + i + 1);
+      process(bufA, t0 + i, i == 0);
+      process(bufB, t0 + i + 1, false);
     } else if (n - i == 1) {
-      process(bufA, t0 + i);
+      process(bufA, t0 + i, i == 0);
+    }
+    if (n <= 0) {                                       // no tile for this wavefront: an empty partial
+#pragma unroll
+      for (int h = 0; h < NH; ++h) m_run[h] = -INFINITY;
     }
   }
 
@@ -408,15 +436,38 @@ __global__ void __launch_bounds__(64) attention_inner_kernel(AttnArgs a, int n_b
       }
     }
   }
+
+  // ---- the window chunk of this wavefront, with a partial slot of its own
+  if (s_idx < win.n_chunks) {
+    __syncthreads();
+    window_pass<NH4, BITS, G, true, false>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
+  }
 }
 
-// op = 0: launch; op = 1: return (as an int cast to hipError_t's slot) nothing -- see resident_waves_z
+// Tiles' worth of time one 64-token window chunk takes (measured; the environment variable is a
+// tuning aid only).
+int window_cost() {
+  static const int v = [] {
+    const char* e = getenv("INNERQ_WINDOW_COST");
+    const int n = e ? atoi(e) : 0;
+    return n > 0 && n < 64 ? n : 18;
+  }();
+  return v;
+}
+
 template <int BITS, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
   const int r = a.n_q_heads / a.n_kv_heads;
-  dim3 grid((unsigned)(n_splits + win.n_chunks), (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
-  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
+  // A window chunk costs its wavefront about as much time as kWindowCost tiles: the wavefronts
+  // that carry one get that many tiles fewer than the common quota.
+  const int n_tiles = (n_both + TILE - 1) / TILE;
+  const int quota = (n_tiles + win.n_chunks * window_cost() + n_splits - 1) / n_splits;
+  int win_tiles = quota > window_cost() ? quota - window_cost() : 0;
+  if (win.n_chunks > 0 && win_tiles > n_tiles / win.n_chunks) win_tiles = n_tiles / win.n_chunks;
+  if (n_splits <= win.n_chunks) return hipErrorInvalidValue;      // the host gives at least one plain wavefront
+  dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
+  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win, win_tiles);
+  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win, win_tiles);
   return hipGetLastError();
 }
 

@@ -66,7 +66,7 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   const int r = a.n_q_heads / a.n_kv_heads;
 
   if ((int)blockIdx.x < win.n_chunks) {
-    window_pass<NH4>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
+    window_pass<NH4, BITS, G, false, true>(a, bh, win.na, win.b0, win.nb, (int)blockIdx.x, win.n_chunks, n_splits + (int)blockIdx.x);
     return;
   }
   const int n_tiles = (n_both + TILE - 1) / TILE;

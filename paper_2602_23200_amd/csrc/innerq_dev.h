@@ -99,8 +99,10 @@ hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
 
 // Fused MFMA kernel for the inner-grouped layout: tokens [w_sink, w_sink + n_both) cut into
 // n_splits contiguous ranges of 64-token tiles, one wavefront each, partial slots 0 .. n_splits.
-// The same launch carries win.n_chunks extra wavefronts per (batch, kv-head) that serve the
-// window token set [0, na) U [b0, b0 + nb) (partial slots n_splits .. n_splits + n_chunks).
+// The window token set [0, na) U [b0, b0 + nb) is cut into win.n_chunks chunks (partial slots
+// n_splits .. n_splits + n_chunks).  The inner kernel gives one chunk each to its first
+// win.n_chunks wavefronts, which take fewer tiles in exchange (n_splits > win.n_chunks); the
+// comparison kernels run the chunks as win.n_chunks extra wavefronts per (batch, kv-head).
 struct WindowSet { long long na, b0, nb; int n_chunks; };
 bool attention_inner_supported(const AttnArgs& a);
 int attention_inner_waves_per_cu(const AttnArgs& a);   // resident wavefronts per compute unit

@@ -43,7 +43,7 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
 }
 
 // fp16 row of token t if that tensor keeps it in fp16 (sink window, recent ring, fp16 store), else null.
-__device__ inline const __half* fp16_row(const TensorView& tv, const AttnArgs& a, long long bh, long long t) {
+__device__ __forceinline__ const __half* fp16_row(const TensorView& tv, const AttnArgs& a, long long bh, long long t) {
   constexpr int D = kHeadDim;
   if (t < tv.n_sink) return tv.sink + (bh * a.w_sink + t) * D;
   const long long row = t - a.w_sink;
@@ -52,22 +52,56 @@ __device__ inline const __half* fp16_row(const TensorView& tv, const AttnArgs& a
   return nullptr;
 }
 
+// Wave-wide reductions: butterflies inside a row of 16 lanes via DPP, then the four rows through
+// scalar registers.
 __device__ inline float window_wave_max(float x) {
-  for (int off = 32; off; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-  return x;
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true)));
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true)));
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
 }
 __device__ inline float window_wave_sum(float x) {
-  for (int off = 32; off; off >>= 1) x += __shfl_xor(x, off);
-  return x;
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return (a + b) + (c + d);
 }
+
+__device__ inline float window_half_lo(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w & 0xffffu))); }
+__device__ inline float window_half_hi(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w >> 16))); }
 
 // Window token set: virtual index v in [0, na + nb) -> token v (v < na) or b0 + v - na.
 // Chunk `chunk` of `n_chunks` equal chunks of that set; partial written to `slot`.
-template <int NH4>
-__device__ inline void window_pass(const AttnArgs& a, long long bh, long long na, long long b0, long long nb,
-                                   int chunk, int n_chunks, int slot) {
+//
+// A window token is kept in fp16 by both tensors, except the fewer than G tokens that the
+// per-token-grouped tensor has already quantised while the per-channel-grouped one still waits
+// for a full group: KQ says the key may be such a packed row (inner grouping), VQ the value
+// (outer grouping).  BITS and G describe those packed rows.
+//
+// Every global load of a 64-token step (the lane's key row, its 16 value-row pieces) is issued
+// before any of them is used, so a step pays one memory round trip; the query set-up runs under
+// that round trip too.
+template <int NH4, int BITS, int G, bool KQ, bool VQ>
+__device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, long long na, long long b0,
+                                            long long nb, int chunk, int n_chunks, int slot) {
   constexpr int D = kHeadDim;
   constexpr int NH = NH4 * 4;
+  constexpr int NG = D / G;
+  constexpr int FPW = 32 / BITS;             // fields per 32-bit word
+  constexpr int WPG = G / FPW;               // words per key group
+  constexpr int KVEC = D * BITS / 128;       // 16-byte pieces of a packed row
+  constexpr uint32_t FMASK = (1u << BITS) - 1u;
+  constexpr float HALFCODE = (float)(1 << (BITS - 1));
   const int lane = threadIdx.x & 63;
   const int b = (int)(bh / a.n_kv_heads), hk = (int)(bh % a.n_kv_heads);
   const int r = a.n_q_heads / a.n_kv_heads;
@@ -77,18 +111,12 @@ __device__ inline void window_pass(const AttnArgs& a, long long bh, long long na
   const long long v1 = v0 + chunk_len < total ? v0 + chunk_len : total;
 
   __shared__ __attribute__((aligned(16))) _Float16 wq[NH][D];       // query, fp16 (exact)
+  __shared__ __attribute__((aligned(16))) float wqf[KQ ? D : 1][NH];   // the same values as fp32, head fastest
+  __shared__ __attribute__((aligned(16))) float wqs[NG][NH];        // their sums over each key group
   __shared__ __attribute__((aligned(16))) float wp[64][NH];         // probabilities of the current 64 tokens
 
-  for (int i = lane; i < NH * D; i += 64) {
-    const int h = i / D, c = i % D;
-    float qv = 0.f;
-    if (h < r) {
-      const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h) * D + c];
-      qv = a.q_scale ? __half2float(__float2half_rn(__half2float(qh) * a.q_scale[hk * D + c])) : __half2float(qh);
-    }
-    wq[h][c] = (_Float16)qv;
-  }
-  __syncthreads();
+  const int cg = lane & 15, tg = lane >> 4;
+  auto token_of = [&](long long v) -> long long { return v < na ? v : b0 + (v - na); };
 
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;    // log2(e) / sqrt(d)
   float m_run[NH], l_run[NH], o[NH][8];
@@ -100,64 +128,139 @@ __device__ inline void window_pass(const AttnArgs& a, long long bh, long long na
     for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
   }
 
-  const int bits = a.bits, G = a.group;
-  const unsigned fmask = (1u << bits) - 1u;
-  const float halfcode = (float)(1 << (bits - 1));
-
   for (long long base = v0; base < v1; base += 64) {
-    // ---- scores: lane = token
+    // ---- all loads of this step
+    w_u32x4 kreg[16], vreg[16];
+    uint32_t ks[2] = {0u, 0u}, kz[2] = {0u, 0u};   // packed key row: scales and zero-points, fp16 pairs
+    bool k_packed = false;
+    uint32_t v_packed = 0u;                        // bit k: value row k of this lane is a packed row
     const long long v = base + lane;
     const bool valid = v < v1;
-    const long long t = valid ? (v < na ? v : b0 + (v - na)) : 0;
+    const int n_here = (int)(v1 - base < 64 ? v1 - base : 64);
+    {
+      const long long t = token_of(valid ? v : v1 - 1);        // idle lanes re-read the last row
+      const __half* krow = fp16_row(a.k, a, bh, t);
+      if (KQ && !krow) {
+        k_packed = true;
+        const long long row = bh * a.capacity + (t - a.w_sink);
+        const w_u32x4* rowp = reinterpret_cast<const w_u32x4*>(a.k.codes + row * (D * BITS / 8));
+#pragma unroll
+        for (int i = 0; i < KVEC; ++i) kreg[i] = rowp[i];
+        const uint32_t* sp = reinterpret_cast<const uint32_t*>(a.k.scales + row * NG);
+#pragma unroll
+        for (int i = 0; i < NG / 2; ++i) ks[i] = sp[i];
+        if (a.k.zeros) {
+          const uint32_t* zp = reinterpret_cast<const uint32_t*>(a.k.zeros + row * NG);
+#pragma unroll
+          for (int i = 0; i < NG / 2; ++i) kz[i] = zp[i];
+        }
+      } else if (krow) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) kreg[i] = *reinterpret_cast<const w_u32x4*>(krow + i * 8);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int j = 4 * k + tg;
+      const long long tj = token_of(base + (j < n_here ? j : n_here - 1));
+      const __half* vrow = fp16_row(a.v, a, bh, tj);
+      if (VQ && !vrow) {
+        v_packed |= 1u << k;
+        const long long row = bh * a.capacity + (tj - a.w_sink);
+        const int c0 = 8 * cg;
+        const uint8_t* cp = a.v.codes + row * (D * BITS / 8) + (c0 * BITS) / 8;
+        const long long si = row * NG + c0 / G;
+        w_u32x4 m = w_u32x4{0u, 0u, 0u, 0u};
+        if constexpr (BITS == 2) m.x = (uint32_t)*reinterpret_cast<const unsigned short*>(cp);
+        else m.x = *reinterpret_cast<const uint32_t*>(cp);
+        m.y = (uint32_t)__half_as_ushort(a.v.scales[si]);
+        if (a.v.zeros) m.z = (uint32_t)__half_as_ushort(a.v.zeros[si]);
+        vreg[k] = m;
+      } else if (vrow) {
+        vreg[k] = *reinterpret_cast<const w_u32x4*>(vrow + 8 * cg);
+      }
+    }
+
+    if (base == v0) {
+      // ---- query: a lane takes 8 consecutive channels of one head (one 16-byte load)
+#pragma unroll
+      for (int rnd = 0; rnd < NH4; ++rnd) {
+        const int idx = rnd * 64 + lane;
+        const int h = idx / (D / 8), c0 = 8 * (idx % (D / 8));
+        w_u32x4 raw = w_u32x4{0u, 0u, 0u, 0u};
+        if (h < r) raw = *reinterpret_cast<const w_u32x4*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + c0);
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float qv = (e & 1) ? window_half_hi(rw[e / 2]) : window_half_lo(rw[e / 2]);
+          if (a.q_scale) qv = __half2float(__float2half_rn(qv * a.q_scale[hk * D + c0 + e]));
+          wq[h][c0 + e] = (_Float16)qv;
+          if constexpr (KQ) wqf[c0 + e][h] = qv;
+          part += qv;
+        }
+        if constexpr (KQ) {
+          // sum over the G/8 lanes that hold one key group (4 lanes: one quad; 8 lanes: two quads)
+          part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0xB1, 0xF, 0xF, true));
+          part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0x4E, 0xF, 0xF, true));
+          if constexpr (G == 64)
+            part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0x141, 0xF, 0xF, true));
+          if ((idx % (G / 8)) == 0) wqs[c0 / G][h] = part;
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- scores: lane = token
     float s[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) s[h] = 0.f;
-    if (valid) {
-      const __half* krow = fp16_row(a.k, a, bh, t);
-      if (krow) {
-#pragma unroll 4
-        for (int i = 0; i < D / 8; ++i) {
-          const w_u32x4 kv = *reinterpret_cast<const w_u32x4*>(krow + i * 8);
-          const uint32_t kw[4] = {kv.x, kv.y, kv.z, kv.w};
+    if (KQ && k_packed) {
+      // a packed row, group by group (Eq. hybrid_dequant): |S| * sum(q * field) + Zeff * sum(q),
+      // the fields taken as they are stored
 #pragma unroll
-          for (int h = 0; h < NH; ++h) {
-            const w_u32x4 qv = *reinterpret_cast<const w_u32x4*>(&wq[h][i * 8]);
-            const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+      for (int g = 0; g < NG; ++g) {
+        float acc[NH];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const w_half2_t kk = __builtin_bit_cast(w_half2_t, kw[e]), qq = __builtin_bit_cast(w_half2_t, qw[e]);
-              s[h] += (float)kk[0] * (float)qq[0];
-              s[h] += (float)kk[1] * (float)qq[1];
+        for (int h = 0; h < NH; ++h) acc[h] = 0.f;
+#pragma unroll
+        for (int wd = 0; wd < WPG; ++wd) {
+          const int wi = g * WPG + wd;
+          const w_u32x4 piece = kreg[wi / 4];
+          const uint32_t w = (wi % 4) == 0 ? piece.x : (wi % 4) == 1 ? piece.y : (wi % 4) == 2 ? piece.z : piece.w;
+#pragma unroll
+          for (int e = 0; e < FPW; ++e) {
+            const float u = (float)((w >> (e * BITS)) & FMASK);
+            const int c = wi * FPW + e;
+#pragma unroll
+            for (int n = 0; n < NH4; ++n) {
+              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[KQ ? c : 0][n * 4]);
+              acc[n * 4 + 0] += q4.x * u; acc[n * 4 + 1] += q4.y * u;
+              acc[n * 4 + 2] += q4.z * u; acc[n * 4 + 3] += q4.w * u;
             }
           }
         }
-      } else if (a.k.form == kPerToken) {
-        // a key that is already quantised while its value still waits in the recent ring:
-        // decode the packed row group by group (Eq. hybrid_dequant)
-        const long long row = t - a.w_sink;
-        const uint32_t* rowp =
-            reinterpret_cast<const uint32_t*>(a.k.codes + ((bh * a.capacity + row) * D * bits) / 8);
-        const int fpw = 32 / bits, wpg = G / fpw;
-        for (int g = 0; g < D / G; ++g) {
-          const long long si = (bh * a.capacity + row) * (D / G) + g;
-          const float sc = __half2float(a.k.scales[si]);
-          const float S = fabsf(sc);
-          const float zeff = (__float_as_uint(sc) >> 31) ? __half2float(a.k.zeros[si]) : -S * halfcode;
-          for (int wd = 0; wd < wpg; ++wd) {
-            const uint32_t w = rowp[g * wpg + wd];
-            for (int e = 0; e < fpw; ++e) {
-              const float x = S * (float)((w >> (e * bits)) & fmask) + zeff;
-              const int c = (g * wpg + wd) * fpw + e;
+        const float sc = (g & 1) ? window_half_hi(ks[g / 2]) : window_half_lo(ks[g / 2]);
+        const float zp = (g & 1) ? window_half_hi(kz[g / 2]) : window_half_lo(kz[g / 2]);
+        const float S = fabsf(sc);
+        const float zeff = (__float_as_uint(sc) >> 31) ? zp : -S * HALFCODE;
 #pragma unroll
-              for (int h = 0; h < NH; ++h) s[h] += (float)wq[h][c] * x;
-            }
+        for (int h = 0; h < NH; ++h) s[h] += S * acc[h] + zeff * wqs[g][h];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t kw[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+          const w_u32x4 qv = *reinterpret_cast<const w_u32x4*>(&wq[h][i * 8]);
+          const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const w_half2_t kk = __builtin_bit_cast(w_half2_t, kw[e]), qq = __builtin_bit_cast(w_half2_t, qw[e]);
+            s[h] += (float)kk[0] * (float)qq[0];
+            s[h] += (float)kk[1] * (float)qq[1];
           }
-        }
-      } else {
-        for (int c = 0; c < D; ++c) {
-          const float kx = fetch_element(a.k, a, bh, t, c);
-#pragma unroll
-          for (int h = 0; h < NH; ++h) s[h] += (float)wq[h][c] * kx;
         }
       }
     }
@@ -173,66 +276,42 @@ __device__ inline void window_pass(const AttnArgs& a, long long bh, long long na
       m_run[h] = m_new;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[h][e] *= alpha;
-      wp[lane][h] = p;
+      wp[lane][h] = p;                                   // 0 for the idle lanes
     }
     __syncthreads();
     // ---- values: 16 lanes share one token row (8 channels = 16 bytes each), 4 rows per load
-    // instruction, every load of the tile in flight at once; lane keeps o[head][8 channels] of
-    // the tokens (4k + lane/16) and the four lane groups are summed at the end.
-    const int n_here = (int)(v1 - base < 64 ? v1 - base : 64);
-    const int cg = lane & 15, tg = lane >> 4;
-    for (int k0 = 0; k0 < 16 && 4 * k0 < n_here; k0 += 8) {      // two batches of 8 rows per lane
-    float x[8][8];
+    // instruction; a lane keeps o[head][8 channels] of the tokens (4k + lane/16) and the four
+    // lane groups are summed at the end.  Rows past the end carry probability 0.
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int j = 4 * (k0 + k) + tg;
+    for (int k = 0; k < 16; ++k) {
+      const int j = 4 * k + tg;
+      float x[8];
+      if (VQ && ((v_packed >> k) & 1u)) {
+        const uint32_t wbits = vreg[k].x;
+        const float sc = window_half_lo(vreg[k].y);
+        const float S = fabsf(sc);
+        const float zeff = (__float_as_uint(sc) >> 31) ? window_half_lo(vreg[k].z) : -S * HALFCODE;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[k][e] = 0.f;
-      if (j < n_here) {
-        const long long vj = base + j;
-        const long long tj = vj < na ? vj : b0 + (vj - na);
-        const __half* vrow = fp16_row(a.v, a, bh, tj);
-        if (vrow) {
-          const w_u32x4 pr = *reinterpret_cast<const w_u32x4*>(vrow + 8 * cg);
-          const uint32_t pw[4] = {pr.x, pr.y, pr.z, pr.w};
+        for (int e = 0; e < 8; ++e) x[e] = S * (float)((wbits >> (e * BITS)) & FMASK) + zeff;
+      } else {
+        const uint32_t pw[4] = {vreg[k].x, vreg[k].y, vreg[k].z, vreg[k].w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const w_half2_t hh = __builtin_bit_cast(w_half2_t, pw[e]);
-            x[k][2 * e] = (float)hh[0];
-            x[k][2 * e + 1] = (float)hh[1];
-          }
-        } else if (a.v.form == kPerToken) {
-          // a value quantised per token while its key still waits in the ring (outer grouping)
-          const long long row = tj - a.w_sink;
-          const int c0 = 8 * cg;
-          const uint8_t* cp = a.v.codes + ((bh * a.capacity + row) * D * bits) / 8 + (c0 * bits) / 8;
-          const unsigned wbits = bits == 2 ? (unsigned)cp[0] | ((unsigned)cp[1] << 8)
-                                           : *reinterpret_cast<const uint32_t*>(cp);
-          const long long si = (bh * a.capacity + row) * (D / G) + c0 / G;
-          const float sc = __half2float(a.v.scales[si]);
-          const float S = fabsf(sc);
-          const float zeff = (__float_as_uint(sc) >> 31) ? __half2float(a.v.zeros[si]) : -S * halfcode;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[k][e] = S * (float)((wbits >> (e * bits)) & fmask) + zeff;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[k][e] = fetch_element(a.v, a, bh, tj, 8 * cg + e);
+        for (int e = 0; e < 4; ++e) {
+          x[2 * e] = window_half_lo(pw[e]);
+          x[2 * e + 1] = window_half_hi(pw[e]);
         }
       }
-    }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int j = 4 * (k0 + k) + tg;                    // rows past n_here carry x = 0
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
         const w_float4_t pj = *reinterpret_cast<const w_float4_t*>(&wp[j][n * 4]);
+        const float pv[4] = {pj.x, pj.y, pj.z, pj.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[n * 4 + i][e] += pj[i] * x[k][e];
+          for (int e = 0; e < 8; ++e) o[n * 4 + i][e] += pv[i] * x[e];
       }
     }
-    }
+    __syncthreads();
   }
 
   // ---- sum the four lane groups; lanes 0..15 then hold channels 8*lane .. 8*lane+7
