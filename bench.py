@@ -39,6 +39,9 @@ def parse():
     p.add_argument("--layers", type=int, default=None, help="layers per step (default: the workload's)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                   help="run only a plain elementwise copy of MIB mebibytes, 10 times (reference for the "
+                        "rocprofv3 FETCH_SIZE / WRITE_SIZE counters), and exit")
     return p.parse_args()
 
 
@@ -145,6 +148,17 @@ def main():
         sys.exit(2)
     import torch
 
+    if args.copy_probe:
+        n = args.copy_probe * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            torch.mul(src, 2.0, out=dst)      # one elementwise kernel: reads 4n bytes, writes 4n bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": True, "bytes_read_per_launch": 4 * n, "bytes_written_per_launch": 4 * n,
+                          "launches": 10}))
+        return
+
     from paper_2602_23200_amd import binding as iq
     from paper_2602_23200_amd import workloads as wl
 
@@ -241,10 +255,14 @@ def main():
     per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
     alg_bytes = per_unit * units
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (a recorded figure:
+    # counters cannot be read from inside this process); null if this workload was not profiled
     traffic = None
-    prof_json = os.path.join(ROOT, "profiles", f"traffic_{w.name}_{args.kind}.json")
-    if os.path.exists(prof_json):
-        traffic = json.load(open(prof_json)).get("hbm_bytes_per_launch")
+    prof_md = os.path.join(ROOT, "profiles", f"attention_{args.kind}_{w.name}_hbm_traffic.md")
+    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode):
+        import re
+        m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(prof_md).read(), re.M)
+        traffic = int(m.group(1)) if m else None
 
     result = {
         "metric": "decode-attention tokens/s (one attention layer step: quantize_append + decode_attention, "

@@ -182,11 +182,13 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
 
 /* Measurement hook (no counterpart in the paper; its Section "Latency" times the fused
  * dequantise-and-multiply kernels on their own, and this lets a benchmark do the same).
- * The next innerq_decode_attention call made by the calling host thread records
- * ev_start immediately before and ev_stop immediately after the launch of its dominant
- * kernel (the fused dequantise + score + value pass over the quantised range) on that
- * call's stream.  Both are hipEvent_t created by the caller with timing enabled; the
- * request is consumed by that one call.  Passing NULL for either cancels a pending request. */
+ * The next innerq_decode_attention call made by the calling host thread attaches
+ * ev_start and ev_stop to the dispatch of its dominant kernel (the fused dequantise +
+ * score + value pass over the quantised range) on that call's stream: they take the
+ * begin and end timestamps of that dispatch, so their difference is the kernel's own
+ * duration as a profiler reports it.  Both are hipEvent_t created by the caller with
+ * timing enabled; the request is consumed by that one call.  Passing NULL for either
+ * cancels a pending request. */
 int innerq_profile_next_attention(void *ev_start, void *ev_stop);
 
 #ifdef __cplusplus

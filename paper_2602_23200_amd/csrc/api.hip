@@ -298,16 +298,17 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   hipEvent_t prof_start = g_prof_start, prof_stop = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (n_splits > 0) {
-    if (prof_start) (void)hipEventRecord(prof_start, stream);
     if (fused) {
+      // the events take the timestamps of the dispatch itself
       const WindowSet win = {n_sink, win_b0, win_b1 - win_b0, n_win};
-      e = fused_kind == 1   ? launch_attention_inner(a, n_both, n_splits, win, stream)
-          : fused_kind == 2 ? launch_attention_fp16(a, n_both, n_splits, win, stream)
-                            : launch_attention_outer(a, n_both, n_splits, win, stream);
+      e = fused_kind == 1   ? launch_attention_inner(a, n_both, n_splits, win, stream, prof_start, prof_stop)
+          : fused_kind == 2 ? launch_attention_fp16(a, n_both, n_splits, win, stream, prof_start, prof_stop)
+                            : launch_attention_outer(a, n_both, n_splits, win, stream, prof_start, prof_stop);
     } else {
+      if (prof_start) (void)hipEventRecord(prof_start, stream);
       e = launch_attention_generic(a, c.w_sink, c.w_sink + n_both, 0, 0, n_splits, 0, stream);
+      if (prof_stop) (void)hipEventRecord(prof_stop, stream);
     }
-    if (prof_stop) (void)hipEventRecord(prof_stop, stream);
     if (e != hipSuccess) return INNERQ_E_HIP;
   }
   if (n_win > 0 && !(fused && n_splits > 0)) {

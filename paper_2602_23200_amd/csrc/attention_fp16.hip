@@ -200,11 +200,15 @@ int attention_fp16_waves_per_cu(const AttnArgs& a) {
 }
 
 hipError_t launch_attention_fp16(const AttnArgs& a, long long n_rows, int n_splits, const WindowSet& win,
-                                 hipStream_t stream) {
+                                 hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int r = a.n_q_heads / a.n_kv_heads;
   dim3 grid((unsigned)(n_splits + win.n_chunks), (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_fp16_kernel<1><<<grid, 64, 0, stream>>>(a, (int)n_rows, n_splits, win);
-  else attention_fp16_kernel<2><<<grid, 64, 0, stream>>>(a, (int)n_rows, n_splits, win);
+  if (r <= 4)
+    hipExtLaunchKernelGGL(attention_fp16_kernel<1>, grid, dim3(64), 0, stream, ev_start, ev_stop, 0, a, (int)n_rows,
+                          n_splits, win);
+  else
+    hipExtLaunchKernelGGL(attention_fp16_kernel<2>, grid, dim3(64), 0, stream, ev_start, ev_stop, 0, a, (int)n_rows,
+                          n_splits, win);
   return hipGetLastError();
 }
 

@@ -456,7 +456,7 @@ int window_cost() {
 }
 
 template <int BITS, int G, bool ZK, bool ZV>
-hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
+hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // A window chunk costs its wavefront about as much time as kWindowCost tiles: the wavefronts
   // that carry one get that many tiles fewer than the common quota.
@@ -466,8 +466,12 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   if (win.n_chunks > 0 && win_tiles > n_tiles / win.n_chunks) win_tiles = n_tiles / win.n_chunks;
   if (n_splits <= win.n_chunks) return hipErrorInvalidValue;      // the host gives at least one plain wavefront
   dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_inner_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win, win_tiles);
-  else attention_inner_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win, win_tiles);
+  if (r <= 4)
+    hipExtLaunchKernelGGL((attention_inner_kernel<BITS, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
+  else
+    hipExtLaunchKernelGGL((attention_inner_kernel<BITS, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
   return hipGetLastError();
 }
 
@@ -483,12 +487,12 @@ int resident_z(const AttnArgs& a) {
 }
 
 template <int BITS, int G>
-hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
+hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, stream);
-  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, stream);
-  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, stream);
-  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, stream);
+  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, L);
+  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, L);
+  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, L);
+  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, L);
 }
 
 template <int BITS, int G>
@@ -523,12 +527,13 @@ int attention_inner_waves_per_cu(const AttnArgs& a) {
 }
 
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int n_both = (int)n_both_ll;
-  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, stream);
-  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, stream);
-  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, stream);
-  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, stream);
+  const Launch L = {stream, ev_start, ev_stop};
+  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, L);
+  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, L);
+  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, L);
+  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, L);
   return hipErrorInvalidValue;
 }
 

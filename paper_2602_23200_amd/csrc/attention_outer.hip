@@ -280,21 +280,25 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
 }
 
 template <int BITS, int G, bool ZK, bool ZV>
-hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
+hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
   dim3 grid((unsigned)(n_splits + win.n_chunks), (unsigned)(a.batch * a.n_kv_heads));
-  if (r <= 4) attention_outer_kernel<BITS, G, 1, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
-  else attention_outer_kernel<BITS, G, 2, ZK, ZV><<<grid, 64, 0, stream>>>(a, n_both, n_splits, win);
+  if (r <= 4)
+    hipExtLaunchKernelGGL((attention_outer_kernel<BITS, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                          L.ev_stop, 0, a, n_both, n_splits, win);
+  else
+    hipExtLaunchKernelGGL((attention_outer_kernel<BITS, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                          L.ev_stop, 0, a, n_both, n_splits, win);
   return hipGetLastError();
 }
 
 template <int BITS, int G>
-hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, hipStream_t stream) {
+hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, stream);
-  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, stream);
-  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, stream);
-  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, stream);
+  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, L);
+  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, L);
+  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, L);
+  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, L);
 }
 
 }  // namespace
@@ -318,12 +322,13 @@ int attention_outer_waves_per_cu(const AttnArgs& a) {
 }
 
 hipError_t launch_attention_outer(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int n_both = (int)n_both_ll;
-  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, stream);
-  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, stream);
-  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, stream);
-  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, stream);
+  const Launch L = {stream, ev_start, ev_stop};
+  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, L);
+  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, L);
+  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, L);
+  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, L);
   return hipErrorInvalidValue;
 }
 

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
@@ -106,19 +107,21 @@ hipError_t launch_attention_merge(const AttnArgs& a, hipStream_t stream);
 struct WindowSet { long long na, b0, nb; int n_chunks; };
 bool attention_inner_supported(const AttnArgs& a);
 int attention_inner_waves_per_cu(const AttnArgs& a);   // resident wavefronts per compute unit
+// ev_start / ev_stop (may be null) take the begin and end timestamps of the kernel dispatch itself.
+struct Launch { hipStream_t stream; hipEvent_t ev_start, ev_stop; };
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
-                                  hipStream_t stream);
+                                  hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // Comparison kernel over an unquantised fp16 store, same launch shape.
 bool attention_fp16_supported(const AttnArgs& a);
 int attention_fp16_waves_per_cu(const AttnArgs& a);
 hipError_t launch_attention_fp16(const AttnArgs& a, long long n_rows, int n_splits, const WindowSet& win,
-                                 hipStream_t stream);
+                                 hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // Comparison kernel over an outer-grouped cache, same launch shape.
 bool attention_outer_supported(const AttnArgs& a);
 int attention_outer_waves_per_cu(const AttnArgs& a);
 hipError_t launch_attention_outer(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
-                                  hipStream_t stream);
+                                  hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 }  // namespace innerq
