@@ -156,14 +156,35 @@ __global__ void __launch_bounds__(64) attention_merge_kernel(AttnArgs a) {
   for (int p = lane; p < P; p += 64) mloc = fmaxf(mloc, ml[2 * p]);
   const float M = window_wave_max(mloc);
   float n0 = 0.f, n1 = 0.f, den = 0.f;
-#pragma unroll 4
-  for (int p = 0; p < P; ++p) {
-    const float m = ml[2 * p];
-    const float w = m == -INFINITY ? 0.f : __expf(m - M);        // an empty partial has m = -inf
-    const float2 ov = *reinterpret_cast<const float2*>(po + (long long)p * D);
-    den += w * ml[2 * p + 1];
-    n0 += w * ov.x;
-    n1 += w * ov.y;
+  // 64 partials at a time: lane p holds the weight of partial base + p, and the loads of the
+  // partial outputs do not depend on the weights, so a whole batch of them is in flight at once
+  for (int base = 0; base < P; base += 64) {
+    const int p_l = base + lane;
+    float w_l = 0.f, l_l = 0.f;
+    if (p_l < P) {
+      const float2 mlv = *reinterpret_cast<const float2*>(ml + 2 * p_l);
+      w_l = mlv.x == -INFINITY ? 0.f : __expf(mlv.x - M);          // an empty partial has m = -inf
+      l_l = mlv.y;
+    }
+    den += window_wave_sum(w_l * l_l);
+    const int n = P - base < 64 ? P - base : 64;
+    // fixed batches of 16 (a loop with a cross-lane read is not unrolled at a run-time trip
+    // count): indices past the end re-read the last partial with the zero weight of an idle lane
+    for (int p0 = 0; p0 < n; p0 += 16) {
+      float2 ov[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int pp = p0 + k < n ? p0 + k : n - 1;
+        ov[k] = *reinterpret_cast<const float2*>(po + (long long)(base + pp) * D);
+      }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_l), p0 + k));
+        w = p0 + k < n ? w : 0.f;
+        n0 += w * ov[k].x;
+        n1 += w * ov[k].y;
+      }
+    }
   }
   const float inv = 1.0f / den;
   if (a.out_is_fp32) {

@@ -59,6 +59,76 @@ __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den
   zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
 }
 
+// The same group quantiser spread over 8 neighbouring lanes (lane `sub` of the group holds the
+// G/8 consecutive values x): the per-element divisions run in parallel, minimum / maximum are
+// exact in any order, and the two error sums are still taken one element after the other in
+// index order (every lane adds the whole chain from shuffled copies), so codes and flag are
+// bit-identical to quantize_group.  Returns this lane's share of the packed fields, shifted to
+// its place inside its 32-bit word and OR-ed over the lanes that share that word.
+template <int CTRL>
+__device__ inline float lane_swap(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ inline uint32_t lane_swap_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int G, int BITS>
+__device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub, int mode, int sym_den_literal,
+                                                __half& scale, __half& zero) {
+  constexpr int E = G / 8;
+  constexpr int QMAX = (1 << BITS) - 1;
+  constexpr int HALF = 1 << (BITS - 1);
+  float mn = x[0], mx = x[0], am = fabsf(x[0]);
+#pragma unroll
+  for (int i = 1; i < E; ++i) {
+    mn = fminf(mn, x[i]);
+    mx = fmaxf(mx, x[i]);
+    am = fmaxf(am, fabsf(x[i]));
+  }
+  // butterflies over the 8 lanes of the group: pairs, quads, the two quads
+  mn = fminf(mn, lane_swap<0xB1>(mn)); mx = fmaxf(mx, lane_swap<0xB1>(mx)); am = fmaxf(am, lane_swap<0xB1>(am));
+  mn = fminf(mn, lane_swap<0x4E>(mn)); mx = fmaxf(mx, lane_swap<0x4E>(mx)); am = fmaxf(am, lane_swap<0x4E>(am));
+  mn = fminf(mn, lane_swap<0x141>(mn)); mx = fmaxf(mx, lane_swap<0x141>(mx)); am = fmaxf(am, lane_swap<0x141>(am));
+  const float den = sym_den_literal ? (float)QMAX : (float)(HALF - 1);
+  const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
+  const __half Ss = __float2half_rn(am / den);
+  const float Saf = h2f(Sa), Ssf = h2f(Ss);
+  uint32_t fa = 0u, fs = 0u;
+  float da[E], ds[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    float ca = fminf(fmaxf(rintf((x[i] - mn) / Saf), 0.f), (float)QMAX);
+    ca = (Saf == 0.f) ? 0.f : ca;
+    float cs = fminf(fmaxf(rintf(x[i] / Ssf), (float)(-HALF)), (float)(HALF - 1));
+    cs = (Ssf == 0.f) ? 0.f : cs;
+    const float ra = Saf * ca + mn;
+    const float rs = Ssf * cs;
+    da[i] = fabsf(x[i] - ra);
+    ds[i] = fabsf(x[i] - rs);
+    fa |= (uint32_t)(int)ca << (i * BITS);
+    fs |= (uint32_t)((int)cs + HALF) << (i * BITS);
+  }
+  float ea = 0.f, es = 0.f;
+  const int first = (int)(threadIdx.x & 63u) & ~7;
+#pragma unroll
+  for (int l = 0; l < 8; ++l) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      ea = ea + __shfl(da[i], first + l);
+      es = es + __shfl(ds[i], first + l);
+    }
+  }
+  const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
+  scale = asym ? __hneg(Sa) : Ss;
+  zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
+  constexpr int LPW = 32 / (E * BITS);                 // lanes that share one 32-bit word
+  uint32_t w = (asym ? fa : fs) << ((sub % LPW) * E * BITS);
+  if constexpr (LPW >= 2) w |= lane_swap_u<0xB1>(w);
+  if constexpr (LPW >= 4) w |= lane_swap_u<0x4E>(w);
+  return w;
+}
+
 // Where the fp16 row of token t (absolute index) of sequence-head bh lives when the quantiser
 // wants it: still in the recent ring if it was appended by an earlier call, else in x_new.
 __device__ inline const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
@@ -113,35 +183,46 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
   constexpr int W = G * BITS / 32;
 
   if (j.form == kPerToken) {
+    // 8 lanes per group, G/8 consecutive channels each
     constexpr int GPR = kHeadDim / G;                    // groups per row
-    if (idx >= BH * n_rows * GPR) return;
-    const int g = (int)(idx % GPR);
-    const long long row = j.row_begin + (idx / GPR) % n_rows;
-    const long long bh = idx / (GPR * n_rows);
+    constexpr int E = G / 8;
+    constexpr int LPW = 32 / (E * BITS);
+    if (idx >= BH * n_rows * GPR * 8) return;
+    const int sub = (int)(idx % 8);
+    const long long gi = idx / 8;
+    const int g = (int)(gi % GPR);
+    const long long row = j.row_begin + (gi / GPR) % n_rows;
+    const long long bh = gi / (GPR * n_rows);
     bool from_new;
-    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G;
-    float x[G];
-#pragma unroll
-    for (int v = 0; v < G / 8; ++v) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(src + v * 8);
+    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G + sub * E;
+    float x[E];
+    if constexpr (E == 4) {
+      const uint2 raw = *reinterpret_cast<const uint2*>(src);
       const __half* h = reinterpret_cast<const __half*>(&raw);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[v * 8 + e] = h2f(h[e]);
+      for (int e = 0; e < 4; ++e) x[e] = h2f(h[e]);
+    } else {
+      const uint4 raw = *reinterpret_cast<const uint4*>(src);
+      const __half* h = reinterpret_cast<const __half*>(&raw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = h2f(h[e]);
     }
     if (from_new && j.normalise) {
-      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G;
+      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G + sub * E;
 #pragma unroll
-      for (int i = 0; i < G; ++i) x[i] = h2f(__float2half_rn(x[i] * inv[i]));
+      for (int i = 0; i < E; ++i) x[i] = h2f(__float2half_rn(x[i] * inv[i]));
     }
-    uint32_t words[W];
     __half s, z;
-    quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
-    uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8) + g * W;
-#pragma unroll
-    for (int i = 0; i < W; ++i) dst[i] = words[i];
-    const long long so = (bh * a.capacity + row) * GPR + g;
-    j.scales[so] = s;
-    if (j.zeros) j.zeros[so] = z;
+    const uint32_t word = quantize_group_lanes<G, BITS>(x, sub, j.mode, a.sym_den_literal, s, z);
+    if (sub % LPW == 0) {
+      uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8) + g * W;
+      dst[sub / LPW] = word;
+    }
+    if (sub == 0) {
+      const long long so = (bh * a.capacity + row) * GPR + g;
+      j.scales[so] = s;
+      if (j.zeros) j.zeros[so] = z;
+    }
   } else if (j.form == kPerChannel) {
     const long long n_groups = n_rows / G;
     if (idx >= BH * n_groups * kHeadDim) return;
@@ -196,7 +277,7 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
     const long long rows = j.row_end - j.row_begin;
     if (rows <= 0) continue;
     long long n = 0;
-    if (j.form == kPerToken) n = BH * rows * (kHeadDim / G);
+    if (j.form == kPerToken) n = BH * rows * (kHeadDim / G) * 8;
     else if (j.form == kPerChannel) n = BH * (rows / G) * kHeadDim;
     else n = BH * rows * (kHeadDim / 8);
     threads = n > threads ? n : threads;
