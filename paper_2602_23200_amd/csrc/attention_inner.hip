@@ -35,6 +35,7 @@
 namespace innerq {
 namespace {
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -45,6 +46,11 @@ constexpr int TILE = 64;                       // tokens per wave iteration (one
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSmScale = 0.08838834764831845f;   // 1/sqrt(128)
+
+// Half `hi` (0 or 1) of a 32-bit word as fp16.
+__device__ inline _Float16 half_of(uint32_t w, int hi) {
+  return __builtin_bit_cast(_Float16, (unsigned short)(hi ? (w >> 16) : (w & 0xffffu)));
+}
 
 template <int BITS>
 struct Fields {
@@ -285,32 +291,40 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
     }
-    // e[h] = score (log2 domain) + position shift - reference level: the exponent of the stored probability
-    float e[NH];
+    // e[h] = score (log2 domain) + position shift - reference level: the exponent of the stored probability.
+    // Per group: |S| * (raw inner sum) + Zeff * (sum of q).  The scale sign bit marks an asymmetric
+    // group, so max(s, 0) is |S| for a symmetric group and 0 for an asymmetric one, and
+    // Zeff = Z - 2^(b-1) * max(s, 0) needs no select (Z is stored as +0 for symmetric groups).
+    // Scales and zero-points enter the FMAs as fp16 sources; the constant factor is applied once.
+    float e[NH], t[NH];
 #pragma unroll
-    for (int h = 0; h < NH; ++h) e[h] = p_shift - m_run[h];
+    for (int h = 0; h < NH; ++h) { e[h] = p_shift - m_run[h]; t[h] = 0.f; }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       const uint32_t spair = cur.ks[g / 2];
-      const __half sh = __ushort_as_half((unsigned short)((g & 1) ? (spair >> 16) : (spair & 0xffffu)));
-      const float sc = __half2float(sh);
-      const bool asym = (g & 1) ? (spair >> 31) : ((spair >> 15) & 1u);
-      const float S = fabsf(sc);
-      float zeff = S * (float)(-HALFCODE);
+      const _Float16 s16 = half_of(spair, g & 1);
+      float zeff;
       if constexpr (has_kz) {
-        const uint32_t zpair = cur.kz[g / 2];
-        const float z = __half2float(__ushort_as_half((unsigned short)((g & 1) ? (zpair >> 16) : (zpair & 0xffffu))));
-        zeff = asym ? z : zeff;
+        const uint32_t mpair = __builtin_bit_cast(
+            uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
+        zeff = __builtin_fmaf((float)half_of(mpair, g & 1), (float)(-HALFCODE), (float)half_of(cur.kz[g / 2], g & 1));
+      } else {
+        zeff = (float)s16 * (float)(-HALFCODE);
       }
-      const float tS = S * (kSmScale * kLog2e * 1048576.0f);            // 2^20 undoes the operand factors
+      const float S = __builtin_fabsf((float)s16);
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
         const float4_t qs = *reinterpret_cast<const float4_t*>(&qsum[n][g][0]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          e[n * 4 + i] = __builtin_fmaf(tS, acc[g][n][i], __builtin_fmaf(zeff, qs[i], e[n * 4 + i]));
+        for (int i = 0; i < 4; ++i) {
+          t[n * 4 + i] = __builtin_fmaf(S, acc[g][n][i], t[n * 4 + i]);
+          e[n * 4 + i] = __builtin_fmaf(zeff, qs[i], e[n * 4 + i]);
+        }
       }
     }
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+      e[h] = __builtin_fmaf(kSmScale * kLog2e * 1048576.0f, t[h], e[h]);   // 2^20 undoes the operand factors
 
     // ================= running softmax (Eq. att:2), probabilities to the operand table =================
     if (tile * TILE + (TILE - 1) > last_row) {         // ragged last tile: lanes past the end weigh nothing
@@ -369,13 +383,16 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
       const uint32_t spair = cur.vs[gi];
-      const float S0 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair & 0xffffu))));
-      const float S1 = fabsf(__half2float(__ushort_as_half((unsigned short)(spair >> 16))));
-      float z0 = S0 * (float)(-HALFCODE), z1 = S1 * (float)(-HALFCODE);
+      const float S0 = __builtin_fabsf((float)half_of(spair, 0)), S1 = __builtin_fabsf((float)half_of(spair, 1));
+      float z0, z1;
       if constexpr (has_vz) {
-        const uint32_t zpair = cur.vz[gi];
-        z0 = ((spair >> 15) & 1u) ? __half2float(__ushort_as_half((unsigned short)(zpair & 0xffffu))) : z0;
-        z1 = (spair >> 31) ? __half2float(__ushort_as_half((unsigned short)(zpair >> 16))) : z1;
+        const uint32_t mpair = __builtin_bit_cast(
+            uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
+        z0 = __builtin_fmaf((float)half_of(mpair, 0), (float)(-HALFCODE), (float)half_of(cur.vz[gi], 0));
+        z1 = __builtin_fmaf((float)half_of(mpair, 1), (float)(-HALFCODE), (float)half_of(cur.vz[gi], 1));
+      } else {
+        z0 = S0 * (float)(-HALFCODE);
+        z1 = S1 * (float)(-HALFCODE);
       }
       // accl = 2^-16 * (sum of the fp16 probabilities of this group); l and o stay in that scale
 #pragma unroll
