@@ -39,6 +39,10 @@ def parse():
     p.add_argument("--layers", type=int, default=None, help="layers per step (default: the workload's)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--asym-frac", type=float, default=None, metavar="F",
+                   help="fill the caches with crafted groups of which a fraction F is quantised asymmetrically "
+                        "in hybrid mode (the rest symmetrically): the density sweep of the flag matrix "
+                        "(paper, Section 'Sparsity of M')")
     p.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                    help="run only a plain elementwise copy of MIB mebibytes, 10 times (reference for the "
                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters), and exit")
@@ -82,12 +86,42 @@ def algorithmic_bytes(w, cfg, iq, n_tokens):
     return per_unit, units
 
 
-def make_instance(torch, iq, w, cfg, layer, n_prefill, gen):
+def crafted_groups(torch, gen, lead, G, bits, frac, device="cuda", return_mask=False):
+    """Groups of G values (last axis) whose hybrid decision is known in advance: with probability
+    frac a group lies exactly on an asymmetric grid of positive values (asymmetric error 0,
+    symmetric error > 0), otherwise exactly on a symmetric grid (symmetric error 0; a tie goes to
+    symmetric).  Every value is exact in fp16."""
+    levels, den = 1 << bits, (1 << (bits - 1)) - 1
+    is_asym = torch.rand(lead, device=device, generator=gen) < frac
+    la = torch.randint(0, levels, (*lead, G), device=device, generator=gen)
+    la[..., 0] = 0
+    la[..., 1] = levels - 1
+    ls = torch.randint(-den, den + 1, (*lead, G), device=device, generator=gen)
+    ls[..., 0] = den
+    x = torch.where(is_asym[..., None], 1.0 + 0.5 * la, 0.125 * ls).half()
+    return (x, is_asym) if return_mask else x
+
+
+def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None):
     """One cache filled with n_prefill synthetic tokens (values per the workload recipe, drawn on the device)."""
     B, Hk, d = w.batch, w.n_kv_heads, w.head_dim
     from paper_2602_23200_amd import workloads as wl
     sigma = torch.from_numpy(wl.key_channel_sigma(w, layer)).to("cuda", torch.float32)      # [Hk, d]
     cache = iq.allocate_cache(cfg)
+    if asym_frac is not None:
+        G = w.group
+        # keys: groups of G channels of one token; values: groups of G tokens of one channel,
+        # aligned at the end of the sink window
+        k = crafted_groups(torch, gen, (B, Hk, n_prefill, d // G), G, w.bits, asym_frac).reshape(B, Hk, n_prefill, d)
+        n_grp = (n_prefill - w.w_sink) // G
+        v = torch.randn((B, Hk, n_prefill, d), device="cuda", generator=gen).half()
+        vg = crafted_groups(torch, gen, (B, Hk, n_grp, d), G, w.bits, asym_frac)          # [B, Hk, n_grp, d, G]
+        v[:, :, w.w_sink:w.w_sink + n_grp * G] = vg.permute(0, 1, 2, 4, 3).reshape(B, Hk, n_grp * G, d)
+        del vg
+        iq.innerq_quantize_append(cache, k.contiguous(), v.contiguous())
+        del k, v
+        torch.cuda.synchronize()
+        return cache
     k = torch.randn((B, Hk, n_prefill, d), device="cuda", generator=gen)
     k.mul_(sigma[None, :, None, :])
     k = k.half()
@@ -180,10 +214,21 @@ def main():
                          w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
-    caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen)
+    caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen, args.asym_frac)
               for i in range(n_inst)]
-    ws = iq.allocate_workspace(cfg)
     B, Hq, Hk, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    flag_density = None
+    if args.asym_frac is not None and kind_id != iq.KIND_FP16:
+        # measured share of asymmetric groups (scale sign bit) over the quantised range of cache 0
+        flag_density = {}
+        for which, name in ((0, "k"), (1, "v")):
+            _, n_q, _ = iq.innerq_partition(cfg, which, caches[0].n_tokens)
+            sc = caches[0].buffers[f"{name}_scales"].view(torch.int16)
+            per_tok = d // w.group if (which == 0) == (kind_id == iq.KIND_INNER) else d
+            rows = n_q if per_tok != d else n_q // w.group
+            sc = sc.view(B * Hk, -1, per_tok)[:, :rows]
+            flag_density[name] = float((sc < 0).float().mean().item())
+    ws = iq.allocate_workspace(cfg)
     # a pool of new tokens / queries so that consecutive steps do not reuse the same inputs
     pool = 16
     k_new = torch.randn((pool, B, Hk, 1, d), device="cuda", generator=gen).half()
@@ -277,6 +322,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "kind": args.kind, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
+                   **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}
+                      if args.asym_frac is not None else {}),
                    "group": w.group, "w_sink": w.w_sink, "w_recent": w.w_recent,
                    "k_mode": ["sym", "asym", "hybrid"][w.k_mode], "v_mode": ["sym", "asym", "hybrid"][w.v_mode],
                    "layers": n_layers, "cache_instances": n_inst},

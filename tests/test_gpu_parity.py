@@ -272,3 +272,39 @@ def test_attention_baseline_configs_full_size_sampled(env, name, slabs):
         assert_cache_equal(g, want_cache, o1, bsel=slice(b, b + 1), hsel=slice(h, h + 1), what=f"slab {b},{h}")
         want = orc.decode_attention(o1, want_cache, q[b:b + 1, h * r:(h + 1) * r])
         assert max_rel_err(got[b:b + 1, h * r:(h + 1) * r], want) <= TOL
+
+
+@pytest.mark.parametrize("frac", [0.05, 0.6])
+def test_crafted_flag_density_cache(env, frac):
+    """The density sweep's crafted cache: flags of the HIP path equal the planned ones and the
+    oracle's, group by group, and attention over it stays within tolerance."""
+    torch, iq = env
+    import bench
+    w = small(n_tokens=4 + 48 + 12 * 32, bits=2, group=32, k_mode=orc.HYBRID, v_mode=orc.HYBRID)
+    o = oracle_config(w)
+    B, Hk, N, d, G = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim, w.group
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    k, km = bench.crafted_groups(torch, gen, (B, Hk, N, d // G), G, w.bits, frac, return_mask=True)
+    k = k.reshape(B, Hk, N, d).contiguous()
+    n_grp = (N - w.w_sink) // G
+    vg, vm = bench.crafted_groups(torch, gen, (B, Hk, n_grp, d), G, w.bits, frac, return_mask=True)
+    v = torch.zeros((B, Hk, N, d), dtype=torch.float16, device="cuda")
+    v[:, :, w.w_sink:w.w_sink + n_grp * G] = vg.permute(0, 1, 2, 4, 3).reshape(B, Hk, n_grp * G, d)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, k, v)
+    torch.cuda.synchronize()
+    want = orc.cache_init_prefill(o, k.cpu().numpy(), v.cpu().numpy())
+    assert_cache_equal(g, want, o, what=f"crafted {frac}")
+    n_qk = N - w.w_sink - w.w_recent
+    got_k = np.signbit(gpu_buffer_as_numpy(g, o, "k_scales"))[:, :, :n_qk]
+    assert np.array_equal(got_k, km.cpu().numpy()[:, :, w.w_sink:w.w_sink + n_qk])
+    n_qv = n_qk // G
+    got_v = np.signbit(gpu_buffer_as_numpy(g, o, "v_scales"))[:, :, :n_qv]
+    assert np.array_equal(got_v, vm.cpu().numpy()[:, :, :n_qv])
+    q = wl.query(w)
+    out = torch.empty((B, w.n_q_heads, d), dtype=torch.float32, device="cuda")
+    iq.innerq_decode_attention(g, to_dev(torch, q), iq.allocate_workspace(gpu_config(o)), out=out)
+    torch.cuda.synchronize()
+    ref = orc.decode_attention(o, want, q, None)
+    assert max_rel_err(out.cpu().numpy(), ref) <= TOL

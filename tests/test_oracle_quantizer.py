@@ -259,3 +259,21 @@ def test_key_norm_definition_and_fold_identity():
     # normalisation flattens the per-channel range: max|K/n| == sqrt(max|K|) == n
     Kn = orc.apply_channel_scale(K, inv_h).astype(np.float32)
     assert np.allclose(np.abs(Kn).max(axis=(0, 2)), np.where(norm_h == 1, np.abs(Kn).max(axis=(0, 2)), norm_h), rtol=2e-3)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_crafted_density_groups_decide_as_planned(bits):
+    """The flag-density sweep of bench.py fills caches with groups whose hybrid decision is fixed
+    by construction (exact asymmetric grid of positive values / exact symmetric grid).  The oracle
+    must take exactly the planned decision for every group and reproduce every value exactly."""
+    import torch
+
+    import bench
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(5)
+    x, planned = bench.crafted_groups(torch, gen, (6, 50), 32, bits, 0.3, device="cpu", return_mask=True)
+    g = x.numpy()
+    u, s, z = orc.quantize_groups(g, bits, orc.HYBRID, 0)
+    assert np.array_equal(np.signbit(s), planned.numpy())
+    assert 0.2 < planned.float().mean().item() < 0.4
+    assert np.array_equal(orc.dequantize_groups(u, s, z, bits), g.astype(np.float64))
