@@ -225,7 +225,13 @@ def dequantize_groups(u: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: 
 # bit packing (this build's storage layout; the paper does not give one)
 # --------------------------------------------------------------------------
 def pack_fields(u: np.ndarray, bits: int) -> np.ndarray:
-    """b-bit fields [..., n] -> bytes [..., n*b/8]; field i sits at bit b*i (little-endian)."""
+    """b-bit fields [..., n] -> bytes [..., n*b/8]; field i sits at bit b*i (little-endian).
+
+    3-bit fields are stored as two planes, one after the other: the low two bits of every field
+    packed as 2-bit fields (n/4 bytes), then the high bits packed as 1-bit fields (n/8 bytes).
+    """
+    if bits == 3:
+        return np.concatenate([pack_fields(u & 3, 2), pack_fields(u >> 2, 1)], axis=-1)
     per = 8 // bits
     u = u.reshape(u.shape[:-1] + (u.shape[-1] // per, per)).astype(np.uint16)
     out = np.zeros(u.shape[:-1], dtype=np.uint16)
@@ -235,6 +241,9 @@ def pack_fields(u: np.ndarray, bits: int) -> np.ndarray:
 
 
 def unpack_fields(p: np.ndarray, bits: int) -> np.ndarray:
+    if bits == 3:
+        n_lo = p.shape[-1] * 2 // 3
+        return unpack_fields(p[..., :n_lo], 2) | (unpack_fields(p[..., n_lo:], 1) << 2)
     per = 8 // bits
     mask = (1 << bits) - 1
     cols = [(p >> (bits * i)) & mask for i in range(per)]

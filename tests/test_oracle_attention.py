@@ -30,8 +30,16 @@ def brute_force_attention(cfg, cache, q16):
     G, bits, ws, wr = cfg.group, cfg.bits, cfg.w_sink, cfg.w_recent
     r = Hq // cfg.n_kv_heads
     N = cache.n_tokens
-    per = 8 // bits
+    per = 8 // bits if bits != 3 else None
     out = np.zeros((B, Hq, d))
+
+    def field_of(row_bytes, i, n):
+        """Field i of a packed run of n fields, read bit by bit from its bytes."""
+        if bits != 3:
+            return (int(row_bytes[i // per]) >> (bits * (i % per))) & ((1 << bits) - 1)
+        lo = (int(row_bytes[i // 4]) >> (2 * (i % 4))) & 3          # plane of 2-bit low parts: n/4 bytes
+        hi = (int(row_bytes[n // 4 + i // 8]) >> (i % 8)) & 1       # then the plane of high bits
+        return lo + 4 * hi
 
     def fp(x):
         return float(x)
@@ -53,12 +61,10 @@ def brute_force_attention(cfg, cache, q16):
         S = getattr(cache, which + "_scales")
         Z = getattr(cache, which + "_zeros")
         if form == orc.FORM_PER_TOKEN:
-            byte = int(codes[b, hk, row, c // per])
-            field = (byte >> (bits * (c % per))) & ((1 << bits) - 1)
+            field = field_of(codes[b, hk, row], c, d)
             s, z = S[b, hk, row, c // G], Z[b, hk, row, c // G]
         else:
-            byte = int(codes[b, hk, row // G, c, (row % G) // per])
-            field = (byte >> (bits * ((row % G) % per))) & ((1 << bits) - 1)
+            field = field_of(codes[b, hk, row // G, c], row % G, G)
             s, z = S[b, hk, row // G, c], Z[b, hk, row // G, c]
         asym = bool(np.signbit(s))
         code = field if asym else field - (1 << (bits - 1))
@@ -78,7 +84,7 @@ def brute_force_attention(cfg, cache, q16):
 
 
 @pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER, orc.KIND_FP16])
-@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.ASYM), (4, orc.SYM)])
+@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.ASYM), (4, orc.SYM), (3, orc.HYBRID), (3, orc.SYM)])
 def test_attention_matches_brute_force_over_stored_bits(kind, bits, mode):
     w = tiny(bits=bits, k_mode=mode, v_mode=mode)
     cfg = oracle_config(w, kind=kind, capacity=96)
@@ -168,19 +174,19 @@ def test_one_dominant_key_selects_its_value_row():
 
 
 def test_more_bits_converge_to_unquantised_attention():
-    """Error against the fp16 cache shrinks with the bit width (2 -> 4 -> 8 bits)."""
+    """Error against the fp16 cache shrinks with the bit width (2 -> 3 -> 4 -> 8 bits)."""
     w = tiny(n_tokens=75, group=16)
     K, V = wl.kv_full(w)
     q = wl.query(w)
     ref_cfg = oracle_config(w, kind=orc.KIND_FP16, capacity=96)
     ref = orc.decode_attention(ref_cfg, orc.cache_init_prefill(ref_cfg, K, V), q)
     errs = []
-    for bits in (2, 4, 8):
+    for bits in (2, 3, 4, 8):
         cfg = oracle_config(w.with_(bits=bits), capacity=96)
         out = orc.decode_attention(cfg, orc.cache_init_prefill(cfg, K, V), q)
         errs.append(np.abs(out - ref).max())
-    assert errs[0] > errs[1] > errs[2]
-    assert errs[2] < 2e-2 * np.abs(ref).max()
+    assert errs[0] > errs[1] > errs[2] > errs[3]
+    assert errs[3] < 2e-2 * np.abs(ref).max()
 
 
 def test_folded_and_unfolded_key_norm_agree():

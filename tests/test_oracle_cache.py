@@ -90,7 +90,7 @@ def test_windows_are_verbatim_and_eviction_cadence(kind, N):
 
 
 @pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER, orc.KIND_FP16])
-@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.SYM), (4, orc.ASYM)])
+@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.SYM), (4, orc.ASYM), (3, orc.HYBRID)])
 def test_chunking_independence_bulk_vs_token_by_token(kind, bits, mode):
     w = small_workload(n_tokens=157, bits=bits, k_mode=mode, v_mode=mode)
     cfg = oracle_config(w, kind=kind, capacity=192)

@@ -34,7 +34,7 @@ def random_groups(seed, n, G, kind):
 KINDS = ["normal", "positive", "outlier", "shifted", "tiny"]
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("kind", KINDS)
 def test_asym_codes_are_nearest_level_brute_force(bits, kind):
     g = random_groups(1, 300, 32, kind)
@@ -58,7 +58,7 @@ def test_asym_codes_are_nearest_level_brute_force(bits, kind):
     assert np.all(c[rows, g.argmax(1)][nz] == (1 << bits) - 1)
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("den", [0, 1])
 @pytest.mark.parametrize("kind", KINDS)
 def test_sym_codes_are_nearest_level_brute_force(bits, den, kind):
@@ -84,7 +84,7 @@ def test_sym_codes_are_nearest_level_brute_force(bits, den, kind):
         assert np.all(c[nz] >= -denom)     # (a denormal fp16 scale may round far enough to reach -2^(b-1))
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("mode", [orc.SYM, orc.ASYM, orc.HYBRID])
 @pytest.mark.parametrize("kind", KINDS)
 def test_round_trip_error_at_most_half_a_step(bits, mode, kind):
@@ -113,7 +113,7 @@ def test_round_trip_literal_denominator_holds_for_unclipped():
         assert (~unclipped).any()          # the literal formula does saturate some elements
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_hybrid_flag_matches_float64_error_comparison(bits):
     near_tie = 0
     for kind in KINDS:
@@ -178,8 +178,22 @@ def test_flag_encoding_sign_bit_and_zero_point(mode):
         assert M.any() and (~M).any()
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_pack_unpack_all_patterns(bits):
+    if bits == 3:
+        # plane layout: every combination of the 8 fields that share one high-bit byte
+        r = np.random.default_rng(1)
+        u = r.integers(0, 8, (4096, 8), dtype=np.uint8)
+        packed = orc.pack_fields(u, 3)
+        assert packed.shape == (4096, 3)
+        assert np.array_equal(orc.unpack_fields(packed, 3), u)
+        # the high-bit byte alone decides which fields are >= 4, the first two bytes the rest
+        hi = np.unpackbits(packed[:, 2:3], axis=1, bitorder="little")
+        assert np.array_equal(hi, (u >= 4).astype(np.uint8))
+        u = r.integers(0, 8, (7, 5, 128), dtype=np.uint8)
+        assert np.array_equal(orc.unpack_fields(orc.pack_fields(u, 3), 3), u)
+        assert orc.pack_fields(u, 3).shape == (7, 5, 48)
+        return
     per = 8 // bits
     # every byte value appears: enumerate all field combinations of one byte
     vals = np.arange(256, dtype=np.uint16)
@@ -228,6 +242,10 @@ def test_effective_bits_match_paper_table():
     assert 0.5 * (3.5 + hybrid_v) == want["InnerQ_Hybrid"]
     # 4-bit symmetric: b + 16/G
     assert bits_per_number(orc.KIND_INNER, "k", 4, orc.SYM) == 4.5
+    # the presets' key half and the Base preset, from the 3-bit stores themselves
+    assert bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM) == 3.5
+    assert 0.5 * (bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM) +
+                  bits_per_number(orc.KIND_INNER, "v", 3, orc.SYM)) == want["InnerQ_Base"]
 
 
 def test_key_norm_definition_and_fold_identity():
@@ -261,7 +279,7 @@ def test_key_norm_definition_and_fold_identity():
     assert np.allclose(np.abs(Kn).max(axis=(0, 2)), np.where(norm_h == 1, np.abs(Kn).max(axis=(0, 2)), norm_h), rtol=2e-3)
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_crafted_density_groups_decide_as_planned(bits):
     """The flag-density sweep of bench.py fills caches with groups whose hybrid decision is fixed
     by construction (exact asymmetric grid of positive values / exact symmetric grid).  The oracle
