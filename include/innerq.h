@@ -40,6 +40,10 @@
  *     codes  u8   [B][Hk][capacity/G][d][G*b/8]   token j of the group at bit b*j
  *     scales fp16 [B][Hk][capacity/G][d]
  *     zeros  fp16 [B][Hk][capacity/G][d]
+ *   b = 3 (the width of the paper's presets, Section "Experimental Setup"): each packed run
+ *   (the d*3/8 bytes of a token row; the G*3/8 bytes of one channel of one token-group) is two
+ *   planes one after the other: the low two bits of every field as 2-bit fields (field i at
+ *   bit 2*i), then the high bits as 1-bit fields (field i at bit i).
  *   fp16 form (kind INNERQ_KIND_FP16): codes fp16 [B][Hk][capacity][d], no scales/zeros.
  *   Store row r holds token w_sink + r.
  *   Stored b-bit field: the unsigned code of an asymmetric group (Eq. asym_quant),
@@ -68,7 +72,7 @@ typedef enum {
   INNERQ_OK = 0,
   INNERQ_E_NULL = -1,        /* a required pointer is NULL */
   INNERQ_E_ARG = -2,         /* inconsistent or out-of-range argument */
-  INNERQ_E_UNSUPPORTED = -3, /* valid in the paper, not built here (e.g. bits = 3) */
+  INNERQ_E_UNSUPPORTED = -3, /* valid in the paper, not built here (e.g. group = 128) */
   INNERQ_E_CAPACITY = -4,    /* the cache cannot hold that many tokens */
   INNERQ_E_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
   INNERQ_E_WORKSPACE = -6,   /* workspace smaller than innerq_workspace_bytes() */
@@ -87,7 +91,7 @@ typedef enum { INNERQ_KIND_INNER = 0, INNERQ_KIND_OUTER = 1, INNERQ_KIND_FP16 = 
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim = 128; n_q_heads % n_kv_heads == 0 */
-  int32_t bits;            /* 2 or 4 */
+  int32_t bits;            /* 2, 3 or 4 */
   int32_t group;           /* 32 or 64; head_dim % group == 0 */
   int32_t w_sink;          /* >= 0 */
   int32_t w_recent;        /* >= 1 */

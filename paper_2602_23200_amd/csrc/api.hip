@@ -39,7 +39,7 @@ int check_config(const innerq_config_t* c) {
   if (c->head_dim % c->group != 0) return INNERQ_E_ARG;          // groups must tile the head dimension
   if (c->capacity_tokens < 1 || c->capacity_tokens % c->group != 0) return INNERQ_E_ARG;
   if (c->head_dim != kHeadDim) return INNERQ_E_UNSUPPORTED;
-  if (c->bits != 2 && c->bits != 4) return INNERQ_E_UNSUPPORTED;  // 3-bit presets of the paper: not built
+  if (c->bits != 2 && c->bits != 3 && c->bits != 4) return INNERQ_E_UNSUPPORTED;
   if (c->group != 32 && c->group != 64) return INNERQ_E_UNSUPPORTED;
   return INNERQ_OK;
 }

@@ -526,7 +526,8 @@ int resident_t(const AttnArgs& a) {
 bool attention_inner_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
-  return a.k.form == kPerToken && a.v.form == kPerChannel && r <= 8 && a.capacity * D <= (1LL << 31);
+  return a.k.form == kPerToken && a.v.form == kPerChannel && (a.bits == 2 || a.bits == 4) && r <= 8 &&
+         a.capacity * D <= (1LL << 31);
 }
 
 int attention_inner_waves_per_cu(const AttnArgs& a) {

@@ -49,8 +49,17 @@ __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den
     const float rs = Ssf * cs;
     ea = ea + fabsf(x[i] - ra);
     es = es + fabsf(x[i] - rs);
-    wa[(i * BITS) / 32] |= (uint32_t)(int)ca << ((i * BITS) % 32);
-    ws[(i * BITS) / 32] |= (uint32_t)((int)cs + HALF) << ((i * BITS) % 32);
+    const uint32_t ua = (uint32_t)(int)ca, us = (uint32_t)((int)cs + HALF);
+    if constexpr (BITS == 3) {
+      // a plane of 2-bit low parts (G/16 words), then a plane of high bits
+      wa[(i * 2) / 32] |= (ua & 3u) << ((i * 2) % 32);
+      ws[(i * 2) / 32] |= (us & 3u) << ((i * 2) % 32);
+      wa[G / 16 + i / 32] |= (ua >> 2) << (i % 32);
+      ws[G / 16 + i / 32] |= (us >> 2) << (i % 32);
+    } else {
+      wa[(i * BITS) / 32] |= ua << ((i * BITS) % 32);
+      ws[(i * BITS) / 32] |= us << ((i * BITS) % 32);
+    }
   }
   const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
 #pragma unroll
@@ -73,9 +82,11 @@ template <int CTRL>
 __device__ inline uint32_t lane_swap_u(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
+// (3-bit fields: the return value is the word of the plane of 2-bit low parts, word_hi that of
+// the plane of high bits, OR-ed over the lanes that share it.)
 template <int G, int BITS>
 __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub, int mode, int sym_den_literal,
-                                                __half& scale, __half& zero) {
+                                                __half& scale, __half& zero, uint32_t& word_hi) {
   constexpr int E = G / 8;
   constexpr int QMAX = (1 << BITS) - 1;
   constexpr int HALF = 1 << (BITS - 1);
@@ -94,7 +105,7 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
-  uint32_t fa = 0u, fs = 0u;
+  uint32_t fa = 0u, fs = 0u, ha = 0u, hs = 0u;
   float da[E], ds[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -106,8 +117,16 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
     const float rs = Ssf * cs;
     da[i] = fabsf(x[i] - ra);
     ds[i] = fabsf(x[i] - rs);
-    fa |= (uint32_t)(int)ca << (i * BITS);
-    fs |= (uint32_t)((int)cs + HALF) << (i * BITS);
+    const uint32_t ua = (uint32_t)(int)ca, us = (uint32_t)((int)cs + HALF);
+    if constexpr (BITS == 3) {
+      fa |= (ua & 3u) << (i * 2);
+      fs |= (us & 3u) << (i * 2);
+      ha |= (ua >> 2) << i;
+      hs |= (us >> 2) << i;
+    } else {
+      fa |= ua << (i * BITS);
+      fs |= us << (i * BITS);
+    }
   }
   float ea = 0.f, es = 0.f;
   const int first = (int)(threadIdx.x & 63u) & ~7;
@@ -122,10 +141,20 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
   const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
   scale = asym ? __hneg(Sa) : Ss;
   zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
-  constexpr int LPW = 32 / (E * BITS);                 // lanes that share one 32-bit word
-  uint32_t w = (asym ? fa : fs) << ((sub % LPW) * E * BITS);
+  constexpr int LB = BITS == 3 ? 2 : BITS;             // bits per field of the (low) plane
+  constexpr int LPW = 32 / (E * LB);                   // lanes that share one 32-bit word of it
+  uint32_t w = (asym ? fa : fs) << ((sub % LPW) * E * LB);
   if constexpr (LPW >= 2) w |= lane_swap_u<0xB1>(w);
   if constexpr (LPW >= 4) w |= lane_swap_u<0x4E>(w);
+  word_hi = 0u;
+  if constexpr (BITS == 3) {
+    constexpr int LPH = 32 / E;                        // lanes per word of the high-bit plane: 8 or 4
+    uint32_t h = (asym ? ha : hs) << ((sub % LPH) * E);
+    h |= lane_swap_u<0xB1>(h);
+    h |= lane_swap_u<0x4E>(h);
+    if constexpr (LPH == 8) h |= lane_swap_u<0x141>(h);
+    word_hi = h;
+  }
   return w;
 }
 
@@ -186,7 +215,8 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
     // 8 lanes per group, G/8 consecutive channels each
     constexpr int GPR = kHeadDim / G;                    // groups per row
     constexpr int E = G / 8;
-    constexpr int LPW = 32 / (E * BITS);
+    constexpr int LB = BITS == 3 ? 2 : BITS;             // bits per field of the (low) plane
+    constexpr int LPW = 32 / (E * LB);
     if (idx >= BH * n_rows * GPR * 8) return;
     const int sub = (int)(idx % 8);
     const long long gi = idx / 8;
@@ -213,10 +243,14 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
       for (int i = 0; i < E; ++i) x[i] = h2f(__float2half_rn(x[i] * inv[i]));
     }
     __half s, z;
-    const uint32_t word = quantize_group_lanes<G, BITS>(x, sub, j.mode, a.sym_den_literal, s, z);
-    if (sub % LPW == 0) {
-      uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8) + g * W;
-      dst[sub / LPW] = word;
+    uint32_t word_hi;
+    const uint32_t word = quantize_group_lanes<G, BITS>(x, sub, j.mode, a.sym_den_literal, s, z, word_hi);
+    // a row is one plane of LB-bit fields over all channels (3-bit: followed by the plane of high bits)
+    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8);
+    if (sub % LPW == 0) rowp[g * (G * LB / 32) + sub / LPW] = word;
+    if constexpr (BITS == 3) {
+      constexpr int LPH = 32 / E;
+      if (sub % LPH == 0) rowp[kHeadDim * 2 / 32 + g * (G / 32) + sub / LPH] = word_hi;
     }
     if (sub == 0) {
       const long long so = (bh * a.capacity + row) * GPR + g;
@@ -372,6 +406,8 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream) {
   if (a.bits == 2 && a.group == 64) return launch_quantize_t<64, 2>(a, stream);
   if (a.bits == 4 && a.group == 32) return launch_quantize_t<32, 4>(a, stream);
   if (a.bits == 4 && a.group == 64) return launch_quantize_t<64, 4>(a, stream);
+  if (a.bits == 3 && a.group == 32) return launch_quantize_t<32, 3>(a, stream);
+  if (a.bits == 3 && a.group == 64) return launch_quantize_t<64, 3>(a, stream);
   return hipErrorInvalidValue;
 }
 

@@ -22,19 +22,21 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
   if (row >= tv.n_quant) return __half2float(tv.ring[(bh * tv.slots + (t % tv.slots)) * D + c]);
   if (tv.form == kFp16) return __half2float(reinterpret_cast<const __half*>(tv.codes)[(bh * a.capacity + row) * D + c]);
   const int bits = a.bits, G = a.group;
-  const unsigned mask = (1u << bits) - 1u;
   long long si;
   unsigned field;
+  // field i of a packed run of n fields that starts at byte address p (3-bit: a plane of 2-bit
+  // low parts, n/4 bytes, then a plane of high bits)
+  auto field_of = [&](const uint8_t* p, int i, int n) -> unsigned {
+    if (bits == 3) return ((p[i / 4] >> (2 * (i % 4))) & 3u) | (((p[n / 4 + i / 8] >> (i % 8)) & 1u) << 2);
+    return (p[(i * bits) / 8] >> ((i * bits) % 8)) & ((1u << bits) - 1u);
+  };
   if (tv.form == kPerToken) {
-    const unsigned byte = tv.codes[((bh * a.capacity + row) * D * bits) / 8 + (c * bits) / 8];
-    field = (byte >> ((c * bits) % 8)) & mask;
+    field = field_of(tv.codes + ((bh * a.capacity + row) * D * bits) / 8, c, D);
     si = (bh * a.capacity + row) * (D / G) + c / G;
   } else {
     const long long tg = row / G;
-    const int j = (int)(row % G);
     si = (bh * (a.capacity / G) + tg) * D + c;
-    const unsigned byte = tv.codes[si * ((G * bits) / 8) + (j * bits) / 8];
-    field = (byte >> ((j * bits) % 8)) & mask;
+    field = field_of(tv.codes + si * ((G * bits) / 8), (int)(row % G), G);
   }
   const float s = __half2float(tv.scales[si]);
   const bool asym = __float_as_uint(s) >> 31;

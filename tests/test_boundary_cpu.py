@@ -54,7 +54,8 @@ def test_validate_config_rejections():
         (dict(n_q_heads=6, n_kv_heads=4), iq.E_ARG),
         (dict(group=48), iq.E_ARG),                  # does not tile head_dim
         (dict(group=16), iq.E_UNSUPPORTED),
-        (dict(bits=3), iq.E_UNSUPPORTED),            # the paper's 3-bit presets are not built
+        (dict(bits=5), iq.E_UNSUPPORTED),            # only 2, 3 and 4 bits are built
+        (dict(bits=8), iq.E_UNSUPPORTED),
         (dict(bits=0), iq.E_ARG),
         (dict(head_dim=64, group=32), iq.E_UNSUPPORTED),
         (dict(w_recent=0), iq.E_ARG),
@@ -125,5 +126,5 @@ def test_calls_reject_bad_arguments_before_any_launch():
     cache.k_scales = 4104
     assert L.innerq_quantize_append(C.byref(c), C.byref(cache), 4096, 4096, 1, None, None) == iq.E_ALIGN
     assert L.innerq_calibrate_key_norm(C.byref(c), 4096, 0, 0, 4096, 4096, None) == iq.E_ARG
-    bad, _ = cfg_of(w, bits=3)
+    bad, _ = cfg_of(w, bits=5)
     assert L.innerq_quantize_append(C.byref(bad), C.byref(cache), 4096, 4096, 1, None, None) == iq.E_UNSUPPORTED

@@ -38,7 +38,7 @@ def to_dev(torch, a):
 
 KINDS = [orc.KIND_INNER, orc.KIND_OUTER, orc.KIND_FP16]
 QUANT_CASES = [(2, 32, orc.HYBRID), (2, 64, orc.HYBRID), (4, 32, orc.HYBRID), (4, 64, orc.ASYM),
-               (2, 32, orc.SYM), (4, 32, orc.SYM)]
+               (2, 32, orc.SYM), (4, 32, orc.SYM), (3, 32, orc.HYBRID), (3, 64, orc.HYBRID), (3, 32, orc.SYM)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
