@@ -33,6 +33,7 @@ def parse():
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--workload", default="llama3_8b_32k")
     p.add_argument("--kind", default="inner", choices=["inner", "outer", "fp16"])
+    p.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="code width (default: the workload's)")
     p.add_argument("--k-mode", default=None, choices=["sym", "asym", "hybrid"])
     p.add_argument("--v-mode", default=None, choices=["sym", "asym", "hybrid"])
     p.add_argument("--instances", type=int, default=8, help="distinct caches rotated through the timed steps")
@@ -199,6 +200,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = wl.WORKLOADS[args.workload]
     modes = {"sym": iq.SYM, "asym": iq.ASYM, "hybrid": iq.HYBRID}
+    if args.bits:
+        w = w.with_(bits=args.bits)
     if args.k_mode:
         w = w.with_(k_mode=modes[args.k_mode])
     if args.v_mode:
@@ -304,7 +307,7 @@ def main():
     # counters cannot be read from inside this process); null if this workload was not profiled
     traffic = None
     prof_md = os.path.join(ROOT, "profiles", f"attention_{args.kind}_{w.name}_hbm_traffic.md")
-    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode):
+    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits):
         import re
         m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(prof_md).read(), re.M)
         traffic = int(m.group(1)) if m else None

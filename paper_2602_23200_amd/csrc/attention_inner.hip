@@ -58,7 +58,7 @@ struct Fields {
   static constexpr int HALF = FPW / 2;         // fields per 16-bit half
   static constexpr int MPW = HALF / 2;         // MFMAs per word (each eats two field positions x two halves)
   static constexpr int SH = BITS == 2 ? 10 : 8;        // one shift brings the upper fields of both halves down
-  static constexpr int NDIRECT = BITS == 2 ? 5 : 2;    // field positions that fit the fp16 mantissa unshifted
+  static constexpr int NDIRECT = BITS == 2 ? 5 : (BITS == 1 ? 8 : 2);   // field positions used unshifted
   static __host__ __device__ constexpr int pos(int f) { return f < NDIRECT ? f : f - NDIRECT; }
   static __host__ __device__ constexpr uint32_t mask(int f) {
     return (uint32_t)(((1u << BITS) - 1u) * 0x00010001u) << (BITS * pos(f));
@@ -106,24 +106,36 @@ __device__ inline float wave_max(float x) {
 template <typename T>
 __device__ inline T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 
-// Everything one wave iteration reads from the quantised store.
+// Everything one wave iteration reads from the quantised store.  3-bit codes are two planes per
+// packed run (2-bit low parts, then 1-bit high parts): a key row is 32 + 16 bytes, one channel of
+// one value group G/4 + G/8 bytes.
 template <int BITS, int G>
 struct TileRegs {
+  static constexpr int LB = BITS == 3 ? 2 : BITS;      // field width of the (low) plane
   static constexpr int KC = D * BITS / 8 / 16;         // 16-byte pieces of one key row
   static constexpr int NG = D / G;                     // key groups per token
   static constexpr int GPT = TILE / G;                 // value token-groups per tile
-  static constexpr int VC = 2 * G * BITS / 8 / 16;     // 16-byte pieces of two channels of one value group
+  static constexpr int CW = G * BITS / 32;             // words of one channel of one value group
+  static constexpr int VW = 2 * CW;                    // ... of this lane's two channels
   u32x4 kc[KC];
   uint32_t ks[NG / 2], kz[NG / 2];                     // fp16 pairs
-  u32x4 vc[GPT][VC];
+  uint32_t vw[GPT][VW];
   uint32_t vs[GPT], vz[GPT];                           // fp16 pairs (this lane's two channels)
+  __device__ uint32_t k_word(int w) const { return kc[w / 4][w % 4]; }                 // low plane: words 0 .. D*LB/32
+  __device__ uint32_t k_high(int w) const { return kc[(D * 2 / 32 + w) / 4][(D * 2 / 32 + w) % 4]; }
+  __device__ uint32_t v_word(int gi, int ch, int w) const { return vw[gi][ch * CW + w]; }
+  __device__ uint32_t v_high(int gi, int ch, int w) const { return vw[gi][ch * CW + G * 2 / 32 + w]; }
 };
 
 template <int BITS, int G, int NH4, bool ZK, bool ZV>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles) {
-  using F = Fields<BITS>;
+  constexpr int LB = BITS == 3 ? 2 : BITS;             // field width of the (low) plane
+  constexpr bool HI = BITS == 3;                       // a plane of high bits follows it
+  using F = Fields<LB>;
+  using F1 = Fields<1>;
   using Regs = TileRegs<BITS, G>;
-  constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC;
+  constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VW = Regs::VW;
+  constexpr int HWG = G / 32;                          // words of the high-bit plane per group
   constexpr int NW = D / F::FPW;                       // words per key row
   constexpr int WPG = G / F::FPW;                      // words per group (key: channels; value: tokens)
   constexpr int TW = TILE / F::FPW;                    // value-side words per tile
@@ -156,6 +168,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(16))) _Float16 qA[NH * D];          // query operand table [head][word][mfma][slot]
   __shared__ __attribute__((aligned(16))) float qsum[NH4][NG][4];       // log2e/sqrt(d) * sum of q over each key group
   __shared__ __attribute__((aligned(16))) _Float16 pA[NH * TILE];       // probability operand table [head][word][mfma][slot]
+  // the same two tables for the plane of high bits (1-bit fields, weight 4): [head][word][mfma][slot]
+  __shared__ __attribute__((aligned(16))) _Float16 qA1[HI ? NH * D : 8];
+  __shared__ __attribute__((aligned(16))) _Float16 pA1[HI ? NH * TILE : 8];
 
   // ---- per-(b, hk) base pointers
   const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * BITS / 8);
@@ -192,9 +207,21 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       int grp = tile * GPT + gi;
       grp = grp > last_group ? last_group : grp;
       const uint32_t ch = (uint32_t)grp * D + 2 * lane;
-      const u32x4* vp = reinterpret_cast<const u32x4*>(vcodes + ch * GB);
+      if constexpr (VW % 4 == 0) {
+        const u32x4* vp = reinterpret_cast<const u32x4*>(vcodes + ch * GB);
 #pragma unroll
-      for (int i = 0; i < VC; ++i) t.vc[gi][i] = stream_load(vp + i);
+        for (int i = 0; i < VW / 4; ++i) {
+          const u32x4 v = stream_load(vp + i);
+          t.vw[gi][4 * i] = v.x; t.vw[gi][4 * i + 1] = v.y; t.vw[gi][4 * i + 2] = v.z; t.vw[gi][4 * i + 3] = v.w;
+        }
+      } else {                                          // 3-bit, G = 32: 24 bytes per lane
+        const u32x2* vp = reinterpret_cast<const u32x2*>(vcodes + ch * GB);
+#pragma unroll
+        for (int i = 0; i < VW / 2; ++i) {
+          const u32x2 v = stream_load(vp + i);
+          t.vw[gi][2 * i] = v.x; t.vw[gi][2 * i + 1] = v.y;
+        }
+      }
       t.vs[gi] = stream_load(reinterpret_cast<const uint32_t*>(vscales + ch));
       if constexpr (has_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + ch));
     }
@@ -230,8 +257,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int c = c0 + e;
       const int word = c / F::FPW, ep = c % F::FPW;
       const int f = ep % F::HALF;
-      const float factor = (float)(1 << (4 + BITS * 4)) / (float)(1 << (BITS * F::pos(f) + BITS * 4));   // 2^(4 - b*pos)
+      const float factor = (float)(1 << (4 + LB * 4)) / (float)(1 << (LB * F::pos(f) + LB * 4));   // 2^(4 - b*pos)
       qA[(h * NW + word) * (MPW * 4) + F::slot(ep)] = (_Float16)(qv * factor);
+      if constexpr (HI) {
+        // 1-bit field at position pos of its half: 2^(pos - 24); weight 4 -> q * 2^(6 - pos)
+        const int word1 = c / 32, ep1 = c % 32;
+        const float factor1 = 64.0f / (float)(1 << F1::pos(ep1 % 16));
+        qA1[(h * (D / 32) + word1) * (F1::MPW * 4) + F1::slot(ep1)] = (_Float16)(qv * factor1);
+      }
     }
     // sum over the G/8 lanes of the group (4 lanes: one quad; 8 lanes: two quads)
     part += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, part), 0xB1, 0xF, 0xF, true));
@@ -248,7 +281,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // reduction and no rescale.  Probabilities are then at most 2^kSlack, times the position
   // factor 2^8: still inside fp16.  l_run and o are kept divided by 2^16 (the raw MFMA scale).
   // The first tile sets the level to its exact maximum.
-  constexpr float kSlack = 6.0f;
+  constexpr float kSlack = HI ? 5.0f : 6.0f;           // (the high-bit plane's factors reach 2^10)
   float m_run[NH], l_run[NH], o[NH][2];
 #pragma unroll
   for (int h = 0; h < NH; ++h) { m_run[h] = 0.f; l_run[h] = 0.f; o[h][0] = 0.f; o[h][1] = 0.f; }
@@ -256,7 +289,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // where this lane's token sits in the probability operand table, and its position factor
   const int p_e = lane % F::FPW;
   const int p_index = (lane / F::FPW) * (MPW * 4) + F::slot(p_e);
-  const float p_shift = (float)(8 - BITS * F::pos(p_e % F::HALF));      // p is stored as p * 2^(8 - b*pos)
+  const float p_shift = (float)(8 - LB * F::pos(p_e % F::HALF));        // p is stored as p * 2^(8 - b*pos)
+  // the same token in the high-bit plane's table: p * 4 * 2^(8 - pos), as a factor on the stored p
+  const int p1_e = lane % 32;
+  const int p1_index = (lane / 32) * (F1::MPW * 4) + F1::slot(p1_e);
+  const float p1_factor = __builtin_amdgcn_exp2f((float)(10 - F1::pos(p1_e % 16)) - p_shift);
   const int qa_lane = (lane & 3) * D;                                   // this lane supplies head (lane & 3) to A
   const int pa_lane = (lane & 3) * TILE;
 
@@ -274,7 +311,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
         const int word = g * WPG + wd;
-        w[g] = cur.kc[word / 4][word % 4];
+        w[g] = cur.k_word(word);
         wsft[g] = w[g] >> F::SH;
       }
 #pragma unroll
@@ -282,11 +319,37 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
           const int word = g * WPG + wd;
-          const half4_t bop = operand<BITS>(w[g], wsft[g], m);
+          const half4_t bop = operand<LB>(w[g], wsft[g], m);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
             const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPW + m) * 4]);
             acc[g][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[g][n], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if constexpr (HI) {
+      // the plane of high bits joins the same chains: its query table carries the weight 4
+#pragma unroll
+      for (int j = 0; j < HWG; ++j) {
+        uint32_t w[NG], wsft[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          w[g] = cur.k_high(g * HWG + j);
+          wsft[g] = w[g] >> F1::SH;
+        }
+#pragma unroll
+        for (int m = 0; m < F1::MPW; ++m) {
+#pragma unroll
+          for (int g = 0; g < NG; ++g) {
+            const int word = g * HWG + j;
+            const half4_t bop = operand<1>(w[g], wsft[g], m);
+#pragma unroll
+            for (int n = 0; n < NH4; ++n) {
+              const half4_t aop =
+                  *reinterpret_cast<const half4_t*>(&qA1[n * 4 * D + qa_lane + (word * F1::MPW + m) * 4]);
+              acc[g][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[g][n], 0, 0, 0);
+            }
           }
         }
       }
@@ -350,7 +413,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     __syncthreads();                                   // previous tile's readers of pA are done
 #pragma unroll
-    for (int h = 0; h < NH; ++h) pA[h * TILE + p_index] = (_Float16)__builtin_amdgcn_exp2f(e[h]);
+    for (int h = 0; h < NH; ++h) {
+      const float p = __builtin_amdgcn_exp2f(e[h]);
+      pA[h * TILE + p_index] = (_Float16)p;
+      if constexpr (HI) pA1[h * TILE + p1_index] = (_Float16)(p * p1_factor);
+    }
     __syncthreads();
 
     // ================= values: lane = two channels (Eq. att:3 with Eq. hybrid_dequant fused) =================
@@ -365,13 +432,13 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
 #pragma unroll
       for (int wd = 0; wd < WPG; ++wd) {
-        const uint32_t wa = cur.vc[gi][wd / 4][wd % 4], wb = cur.vc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
+        const uint32_t wa = cur.v_word(gi, 0, wd), wb = cur.v_word(gi, 1, wd);
         const uint32_t was = wa >> F::SH, wbs = wb >> F::SH;
 #pragma unroll
         for (int m = 0; m < MPW; ++m) {
-          const half4_t b0 = operand<BITS>(wa, was, m);
-          const half4_t b1 = operand<BITS>(wb, wbs, m);
-          const half4_t b1s = ones_operand<BITS>(m);
+          const half4_t b0 = operand<LB>(wa, was, m);
+          const half4_t b1 = operand<LB>(wb, wbs, m);
+          const half4_t b1s = ones_operand<LB>(m);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
             const half4_t aop =
@@ -379,6 +446,25 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             acc0[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b0, acc0[n], 0, 0, 0);
             acc1[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1, acc1[n], 0, 0, 0);
             accl[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1s, accl[n], 0, 0, 0);
+          }
+        }
+      }
+      if constexpr (HI) {
+#pragma unroll
+        for (int j = 0; j < HWG; ++j) {
+          const uint32_t wa = cur.v_high(gi, 0, j), wb = cur.v_high(gi, 1, j);
+          const uint32_t was = wa >> F1::SH, wbs = wb >> F1::SH;
+#pragma unroll
+          for (int m = 0; m < F1::MPW; ++m) {
+            const half4_t b0 = operand<1>(wa, was, m);
+            const half4_t b1 = operand<1>(wb, wbs, m);
+#pragma unroll
+            for (int n = 0; n < NH4; ++n) {
+              const half4_t aop = *reinterpret_cast<const half4_t*>(
+                  &pA1[n * 4 * TILE + pa_lane + ((gi * HWG + j) * F1::MPW + m) * 4]);
+              acc0[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b0, acc0[n], 0, 0, 0);
+              acc1[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1, acc1[n], 0, 0, 0);
+            }
           }
         }
       }
@@ -526,18 +612,20 @@ int resident_t(const AttnArgs& a) {
 bool attention_inner_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
-  return a.k.form == kPerToken && a.v.form == kPerChannel && (a.bits == 2 || a.bits == 4) && r <= 8 &&
+  return a.k.form == kPerToken && a.v.form == kPerChannel && (a.bits >= 2 && a.bits <= 4) && r <= 8 &&
          a.capacity * D <= (1LL << 31);
 }
 
 int attention_inner_waves_per_cu(const AttnArgs& a) {
   // cached per (bits, group, zero flags, head tile): the answer depends on the kernel instance only
-  static int cache[2][2][2][2][2] = {};
+  static int cache[3][2][2][2][2] = {};
   const int r = a.n_q_heads / a.n_kv_heads;
-  int& c = cache[a.bits == 4][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
+  int& c = cache[a.bits - 2][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
   if (c == 0) {
     if (a.bits == 2 && a.group == 32) c = resident_t<2, 32>(a);
     else if (a.bits == 2 && a.group == 64) c = resident_t<2, 64>(a);
+    else if (a.bits == 3 && a.group == 32) c = resident_t<3, 32>(a);
+    else if (a.bits == 3 && a.group == 64) c = resident_t<3, 64>(a);
     else if (a.bits == 4 && a.group == 32) c = resident_t<4, 32>(a);
     else c = resident_t<4, 64>(a);
   }
@@ -552,6 +640,8 @@ hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_
   if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, L);
   if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, L);
   if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, L);
+  if (a.bits == 3 && a.group == 32) return launch_t<3, 32>(a, n_both, n_splits, win, L);
+  if (a.bits == 3 && a.group == 64) return launch_t<3, 64>(a, n_both, n_splits, win, L);
   return hipErrorInvalidValue;
 }
 

@@ -225,6 +225,24 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         float acc[NH];
 #pragma unroll
         for (int h = 0; h < NH; ++h) acc[h] = 0.f;
+        if constexpr (BITS == 3) {
+          // a plane of 2-bit low parts (D/16 words), then a plane of high bits (D/32 words)
+#pragma unroll
+          for (int cc = 0; cc < G; ++cc) {
+            const int c = g * G + cc;
+            const int wl = c / 16, wh = D / 16 + c / 32;
+            const w_u32x4 pl = kreg[wl / 4], ph = kreg[wh / 4];
+            const uint32_t lo = (wl % 4) == 0 ? pl.x : (wl % 4) == 1 ? pl.y : (wl % 4) == 2 ? pl.z : pl.w;
+            const uint32_t hi = (wh % 4) == 0 ? ph.x : (wh % 4) == 1 ? ph.y : (wh % 4) == 2 ? ph.z : ph.w;
+            const float u = (float)(((lo >> (2 * (c % 16))) & 3u) | (((hi >> (c % 32)) & 1u) << 2));
+#pragma unroll
+            for (int n = 0; n < NH4; ++n) {
+              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[c][n * 4]);
+              acc[n * 4 + 0] += q4.x * u; acc[n * 4 + 1] += q4.y * u;
+              acc[n * 4 + 2] += q4.z * u; acc[n * 4 + 3] += q4.w * u;
+            }
+          }
+        } else {
 #pragma unroll
         for (int wd = 0; wd < WPG; ++wd) {
           const int wi = g * WPG + wd;
@@ -236,11 +254,12 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
             const int c = wi * FPW + e;
 #pragma unroll
             for (int n = 0; n < NH4; ++n) {
-              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[KQ ? c : 0][n * 4]);
+              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[c][n * 4]);
               acc[n * 4 + 0] += q4.x * u; acc[n * 4 + 1] += q4.y * u;
               acc[n * 4 + 2] += q4.z * u; acc[n * 4 + 3] += q4.w * u;
             }
           }
+        }
         }
         const float sc = (g & 1) ? window_half_hi(ks[g / 2]) : window_half_lo(ks[g / 2]);
         const float zp = (g & 1) ? window_half_hi(kz[g / 2]) : window_half_lo(kz[g / 2]);
