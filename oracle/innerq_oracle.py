@@ -63,6 +63,12 @@ class Config:
     sym_denominator: int = 0     # 0: 2^(b-1)-1 ; 1: 2^b-1 (the formula as printed)
     kind: int = KIND_INNER
     capacity_tokens: int = 0
+    v_bits: int = 0              # width of the value codes; 0: same as bits (the key width)
+
+    def bits_of(self, which: str) -> int:
+        """Code width of tensor 'k' or 'v' (the paper's presets pair 3-bit keys with 2- or 3-bit
+        values: Section "Experimental Setup")."""
+        return self.v_bits if (which == "v" and self.v_bits) else self.bits
 
     def form(self, which: str) -> int:
         """Grouping form of tensor 'k' or 'v'.
@@ -269,7 +275,7 @@ class Cache:
 
 
 def _store_shapes(cfg: Config, which: str):
-    B, H, d, G, b, cap = cfg.batch, cfg.n_kv_heads, cfg.head_dim, cfg.group, cfg.bits, cfg.capacity_tokens
+    B, H, d, G, b, cap = cfg.batch, cfg.n_kv_heads, cfg.head_dim, cfg.group, cfg.bits_of(which), cfg.capacity_tokens
     form = cfg.form(which)
     if form == FORM_FP16:
         return (B, H, cap, d), None
@@ -298,7 +304,7 @@ def _quantise_into_store(cfg: Config, cache: Cache, which: str, x16: np.ndarray,
     scales = getattr(cache, which + "_scales")
     zeros = getattr(cache, which + "_zeros")
     B, H, T, d = x16.shape
-    G, b = cfg.group, cfg.bits
+    G, b = cfg.group, cfg.bits_of(which)
     form, mode = cfg.form(which), cfg.mode(which)
     if T == 0:
         return
@@ -385,7 +391,7 @@ def quantize_append(cfg: Config, cache: Cache, k_new: np.ndarray, v_new: np.ndar
 def effective_tensor(cfg: Config, cache: Cache, which: str, b: int, hk: int) -> np.ndarray:
     """All N cached rows of K or V of one (batch, kv-head) as the decoder sees them, float64 [N, d]."""
     N = cache.n_tokens
-    d, G, bits = cfg.head_dim, cfg.group, cfg.bits
+    d, G, bits = cfg.head_dim, cfg.group, cfg.bits_of(which)
     n_s, n_q, n_r = partition(cfg, which, N)
     out = np.empty((N, d), dtype=np.float64)
     out[:n_s] = getattr(cache, which + "_sink")[b, hk, :n_s]

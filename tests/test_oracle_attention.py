@@ -27,14 +27,14 @@ def tiny(**kw):
 def brute_force_attention(cfg, cache, q16):
     """Loops only: decode each stored element from its bits, then softmax attention."""
     B, Hq, d = q16.shape
-    G, bits, ws, wr = cfg.group, cfg.bits, cfg.w_sink, cfg.w_recent
+    G, ws, wr = cfg.group, cfg.w_sink, cfg.w_recent
     r = Hq // cfg.n_kv_heads
     N = cache.n_tokens
-    per = 8 // bits if bits != 3 else None
     out = np.zeros((B, Hq, d))
 
-    def field_of(row_bytes, i, n):
+    def field_of(row_bytes, i, n, bits):
         """Field i of a packed run of n fields, read bit by bit from its bytes."""
+        per = 8 // bits
         if bits != 3:
             return (int(row_bytes[i // per]) >> (bits * (i % per))) & ((1 << bits) - 1)
         lo = (int(row_bytes[i // 4]) >> (2 * (i % 4))) & 3          # plane of 2-bit low parts: n/4 bytes
@@ -60,11 +60,12 @@ def brute_force_attention(cfg, cache, q16):
             return fp(codes[b, hk, row, c])
         S = getattr(cache, which + "_scales")
         Z = getattr(cache, which + "_zeros")
+        bits = cfg.v_bits if (which == "v" and cfg.v_bits) else cfg.bits
         if form == orc.FORM_PER_TOKEN:
-            field = field_of(codes[b, hk, row], c, d)
+            field = field_of(codes[b, hk, row], c, d, bits)
             s, z = S[b, hk, row, c // G], Z[b, hk, row, c // G]
         else:
-            field = field_of(codes[b, hk, row // G, c], row % G, G)
+            field = field_of(codes[b, hk, row // G, c], row % G, G, bits)
             s, z = S[b, hk, row // G, c], Z[b, hk, row // G, c]
         asym = bool(np.signbit(s))
         code = field if asym else field - (1 << (bits - 1))
@@ -84,10 +85,14 @@ def brute_force_attention(cfg, cache, q16):
 
 
 @pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER, orc.KIND_FP16])
-@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.ASYM), (4, orc.SYM), (3, orc.HYBRID), (3, orc.SYM)])
+@pytest.mark.parametrize("bits,mode", [(2, orc.HYBRID), (4, orc.ASYM), (4, orc.SYM), (3, orc.HYBRID), (3, orc.SYM),
+                                       ((3, 2), orc.HYBRID), ((2, 4), orc.SYM)])
 def test_attention_matches_brute_force_over_stored_bits(kind, bits, mode):
+    v_bits = 0
+    if isinstance(bits, tuple):
+        bits, v_bits = bits
     w = tiny(bits=bits, k_mode=mode, v_mode=mode)
-    cfg = oracle_config(w, kind=kind, capacity=96)
+    cfg = oracle_config(w, kind=kind, capacity=96, v_bits=v_bits)
     K, V = wl.kv_full(w)
     cache = orc.cache_new(cfg)
     orc.quantize_append(cfg, cache, K, V)

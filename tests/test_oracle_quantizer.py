@@ -225,8 +225,8 @@ def test_effective_bits_match_paper_table():
         name, val = line.split()
         want[name] = float(val)
 
-    def bits_per_number(kind, which, bits, mode):
-        cfg = orc.Config(1, 4, 1, 128, bits, 32, 4, 32, mode, mode, 0, kind, 1024)
+    def bits_per_number(kind, which, bits, mode, v_bits=0):
+        cfg = orc.Config(1, 4, 1, 128, bits, 32, 4, 32, mode, mode, 0, kind, 1024, v_bits)
         cs, ss = orc._store_shapes(cfg, which)
         n = 1024 * 128
         total = np.prod(cs) + 2 * np.prod(ss) * (1 if mode == orc.SYM else 2)
@@ -242,6 +242,11 @@ def test_effective_bits_match_paper_table():
     assert 0.5 * (3.5 + hybrid_v) == want["InnerQ_Hybrid"]
     # 4-bit symmetric: b + 16/G
     assert bits_per_number(orc.KIND_INNER, "k", 4, orc.SYM) == 4.5
+    # Hybrid and Small presets as one configuration each: 3-bit symmetric keys, 2-bit values
+    assert 0.5 * (bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM, 2) +
+                  bits_per_number(orc.KIND_INNER, "v", 3, orc.SYM, 2)) == want["InnerQ_Small"]
+    assert 0.5 * (bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM, 2) +
+                  bits_per_number(orc.KIND_INNER, "v", 3, orc.HYBRID, 2)) == want["InnerQ_Hybrid"]
     # the presets' key half and the Base preset, from the 3-bit stores themselves
     assert bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM) == 3.5
     assert 0.5 * (bits_per_number(orc.KIND_INNER, "k", 3, orc.SYM) +
