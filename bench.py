@@ -34,6 +34,8 @@ def parse():
     p.add_argument("--workload", default="llama3_8b_32k")
     p.add_argument("--kind", default="inner", choices=["inner", "outer", "fp16"])
     p.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="code width (default: the workload's)")
+    p.add_argument("--v-bits", type=int, default=0, choices=[0, 2, 3, 4],
+                   help="width of the value codes when it differs from the keys' (0: the same)")
     p.add_argument("--k-mode", default=None, choices=["sym", "asym", "hybrid"])
     p.add_argument("--v-mode", default=None, choices=["sym", "asym", "hybrid"])
     p.add_argument("--instances", type=int, default=8, help="distinct caches rotated through the timed steps")
@@ -81,8 +83,8 @@ def algorithmic_bytes(w, cfg, iq, n_tokens):
         per_unit = 2 * d * 2
     else:
         per_unit = 0
-        for mode in (cfg.k_mode, cfg.v_mode):
-            per_unit += d * b // 8 + (d // G) * 2 * (1 if mode == iq.SYM else 2)
+        for mode, bits in ((cfg.k_mode, cfg.bits), (cfg.v_mode, cfg.v_bits or cfg.bits)):
+            per_unit += d * bits // 8 + (d // G) * 2 * (1 if mode == iq.SYM else 2)
     units = w.batch * w.n_kv_heads * n_both
     return per_unit, units
 
@@ -138,7 +140,7 @@ def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None):
     return cache
 
 
-def cpu_baseline(w, kind_id, seconds):
+def cpu_baseline(w, kind_id, seconds, v_bits=0):
     """The CPU oracle timed on a bounded sample of the same workload: whole (batch, kv-head) slabs,
     each one decode step (append one token + attention for the slab's query heads)."""
     import numpy as np
@@ -151,7 +153,7 @@ def cpu_baseline(w, kind_id, seconds):
     w1 = w.with_(batch=1, n_kv_heads=1, n_q_heads=r)
     cap = -(-(w.n_tokens + 2 * w.group) // w.group) * w.group
     o = orc.Config(1, r, 1, w.head_dim, w.bits, w.group, w.w_sink, w.w_recent, w.k_mode, w.v_mode, 0,
-                   kind_id, cap)
+                   kind_id, cap, v_bits)
     total_slabs = w.batch * w.n_kv_heads * w.n_layers
     done, spent, wall0 = 0, 0.0, time.perf_counter()
     with threadpool_limits(limits=1):
@@ -214,7 +216,7 @@ def main():
     per_inst_appends = -(-(K + W + 2 * K) // n_inst) + 1 if n_layers == 1 else (K + W + 2 * K) + 1
     cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
     cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
-                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap)
+                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
     caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen, args.asym_frac)
@@ -307,7 +309,7 @@ def main():
     # counters cannot be read from inside this process); null if this workload was not profiled
     traffic = None
     prof_md = os.path.join(ROOT, "profiles", f"attention_{args.kind}_{w.name}_hbm_traffic.md")
-    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits):
+    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits or args.v_bits):
         import re
         m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(prof_md).read(), re.M)
         traffic = int(m.group(1)) if m else None
@@ -325,6 +327,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "kind": args.kind, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
+                   "v_bits": args.v_bits or w.bits,
                    **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}
                       if args.asym_frac is not None else {}),
                    "group": w.group, "w_sink": w.w_sink, "w_recent": w.w_recent,
@@ -340,7 +343,7 @@ def main():
                          "attention_only": attn_ms, "append_only": append_ms},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, kind_id, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(w, kind_id, args.cpu_seconds, args.v_bits)
     print(json.dumps(result))
 
 

@@ -91,7 +91,7 @@ typedef enum { INNERQ_KIND_INNER = 0, INNERQ_KIND_OUTER = 1, INNERQ_KIND_FP16 = 
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim = 128; n_q_heads % n_kv_heads == 0 */
-  int32_t bits;            /* 2, 3 or 4 */
+  int32_t bits;            /* width of the key codes (and of the value codes unless v_bits is set): 2, 3 or 4 */
   int32_t group;           /* 32 or 64; head_dim % group == 0 */
   int32_t w_sink;          /* >= 0 */
   int32_t w_recent;        /* >= 1 */
@@ -101,6 +101,9 @@ typedef struct {
                               at -2^(b-1) and 2^(b-1)-1) */
   int32_t kind;            /* innerq_kind_t */
   int64_t capacity_tokens; /* most tokens the cache may ever hold; a multiple of group */
+  int32_t v_bits;          /* width of the value codes: 2, 3 or 4; 0 = same as bits, which is then the
+                              width of both (the paper's Hybrid and Small presets pair 3-bit keys
+                              with 2-bit values: Section "Experimental Setup") */
 } innerq_config_t;
 
 typedef struct {

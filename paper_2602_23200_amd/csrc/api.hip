@@ -40,6 +40,8 @@ int check_config(const innerq_config_t* c) {
   if (c->capacity_tokens < 1 || c->capacity_tokens % c->group != 0) return INNERQ_E_ARG;
   if (c->head_dim != kHeadDim) return INNERQ_E_UNSUPPORTED;
   if (c->bits != 2 && c->bits != 3 && c->bits != 4) return INNERQ_E_UNSUPPORTED;
+  if (c->v_bits < 0 || c->v_bits > 8) return INNERQ_E_ARG;
+  if (c->v_bits != 0 && c->v_bits != 2 && c->v_bits != 3 && c->v_bits != 4) return INNERQ_E_UNSUPPORTED;
   if (c->group != 32 && c->group != 64) return INNERQ_E_UNSUPPORTED;
   return INNERQ_OK;
 }
@@ -77,6 +79,7 @@ TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which,
   v.form = form_of(c.kind, which);
   v.slots = ring_slots(c, which);
   v.n_sink = (int)p.n_sink;
+  v.bits = bits_of(c, which);
   v.n_quant = p.n_quant;
   return v;
 }
@@ -132,7 +135,7 @@ size_t innerq_buffer_bytes(const innerq_config_t* cfg, int which) {
   const int form = form_of(c.kind, t);
   switch (which) {
     case INNERQ_BUF_K_CODES: case INNERQ_BUF_V_CODES:
-      return form == kFp16 ? BH * cap * d * 2 : BH * cap * d * (size_t)c.bits / 8;
+      return form == kFp16 ? BH * cap * d * 2 : BH * cap * d * (size_t)bits_of(c, t) / 8;
     case INNERQ_BUF_K_SCALES: case INNERQ_BUF_V_SCALES:
       return form == kFp16 ? 0 : BH * cap * d / (size_t)c.group * 2;
     case INNERQ_BUF_K_ZEROS: case INNERQ_BUF_V_ZEROS:
@@ -190,7 +193,7 @@ int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, co
 
   QuantArgs a;
   a.inv_norm = k_inv_norm;
-  a.batch = cfg->batch; a.n_kv_heads = cfg->n_kv_heads; a.bits = cfg->bits; a.group = cfg->group;
+  a.batch = cfg->batch; a.n_kv_heads = cfg->n_kv_heads; a.group = cfg->group;
   a.w_sink = cfg->w_sink; a.sym_den_literal = cfg->sym_denominator;
   a.capacity = cfg->capacity_tokens; a.n_old = n0; a.t_new = t_new;
   for (int w = 0; w < 2; ++w) {
@@ -202,6 +205,7 @@ int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, co
     j.ring = static_cast<__half*>(w == 0 ? cache->k_recent : cache->v_recent);
     j.x_new = static_cast<const __half*>(w == 0 ? k_new : v_new);
     j.form = form_of(cfg->kind, w);
+    j.bits = bits_of(*cfg, w);
     j.mode = w == 0 ? cfg->k_mode : cfg->v_mode;
     j.slots = ring_slots(*cfg, w);
     // rows that leave the recent window during this call (oldest first)
@@ -239,7 +243,7 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   a.q_scale = q_scale;
   a.out = out; a.out_is_fp32 = out_is_fp32;
   a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
-  a.bits = c.bits; a.group = c.group; a.w_sink = c.w_sink;
+  a.bits = bits_of(c, 0); a.v_bits = bits_of(c, 1); a.group = c.group; a.w_sink = c.w_sink;
   a.capacity = c.capacity_tokens; a.n_tokens = N;
 
   // Tokens [w_sink, w_sink + n_both) are in the quantised store for both K and V: the split-K

@@ -109,38 +109,38 @@ __device__ inline T stream_load(const T* p) { return __builtin_nontemporal_load(
 // Everything one wave iteration reads from the quantised store.  3-bit codes are two planes per
 // packed run (2-bit low parts, then 1-bit high parts): a key row is 32 + 16 bytes, one channel of
 // one value group G/4 + G/8 bytes.
-template <int BITS, int G>
+template <int KB, int VB, int G>
 struct TileRegs {
-  static constexpr int LB = BITS == 3 ? 2 : BITS;      // field width of the (low) plane
-  static constexpr int KC = D * BITS / 8 / 16;         // 16-byte pieces of one key row
+  static constexpr int KC = D * KB / 8 / 16;           // 16-byte pieces of one key row
   static constexpr int NG = D / G;                     // key groups per token
   static constexpr int GPT = TILE / G;                 // value token-groups per tile
-  static constexpr int CW = G * BITS / 32;             // words of one channel of one value group
+  static constexpr int CW = G * VB / 32;               // words of one channel of one value group
   static constexpr int VW = 2 * CW;                    // ... of this lane's two channels
   u32x4 kc[KC];
   uint32_t ks[NG / 2], kz[NG / 2];                     // fp16 pairs
   uint32_t vw[GPT][VW];
   uint32_t vs[GPT], vz[GPT];                           // fp16 pairs (this lane's two channels)
-  __device__ uint32_t k_word(int w) const { return kc[w / 4][w % 4]; }                 // low plane: words 0 .. D*LB/32
+  __device__ uint32_t k_word(int w) const { return kc[w / 4][w % 4]; }                 // (low) plane of the row
   __device__ uint32_t k_high(int w) const { return kc[(D * 2 / 32 + w) / 4][(D * 2 / 32 + w) % 4]; }
   __device__ uint32_t v_word(int gi, int ch, int w) const { return vw[gi][ch * CW + w]; }
   __device__ uint32_t v_high(int gi, int ch, int w) const { return vw[gi][ch * CW + G * 2 / 32 + w]; }
 };
 
-template <int BITS, int G, int NH4, bool ZK, bool ZV>
+// KB, VB: widths of the key and value codes.
+template <int KB, int VB, int G, int NH4, bool ZK, bool ZV>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles) {
-  constexpr int LB = BITS == 3 ? 2 : BITS;             // field width of the (low) plane
-  constexpr bool HI = BITS == 3;                       // a plane of high bits follows it
-  using F = Fields<LB>;
+  constexpr int LBK = KB == 3 ? 2 : KB, LBV = VB == 3 ? 2 : VB;   // field width of the (low) plane
+  constexpr bool HIK = KB == 3, HIV = VB == 3;                     // a plane of high bits follows it
+  using FK = Fields<LBK>;
+  using FV = Fields<LBV>;
   using F1 = Fields<1>;
-  using Regs = TileRegs<BITS, G>;
+  using Regs = TileRegs<KB, VB, G>;
   constexpr int NG = Regs::NG, GPT = Regs::GPT, KC = Regs::KC, VW = Regs::VW;
   constexpr int HWG = G / 32;                          // words of the high-bit plane per group
-  constexpr int NW = D / F::FPW;                       // words per key row
-  constexpr int WPG = G / F::FPW;                      // words per group (key: channels; value: tokens)
-  constexpr int TW = TILE / F::FPW;                    // value-side words per tile
-  constexpr int MPW = F::MPW;
-  constexpr int HALFCODE = 1 << (BITS - 1);
+  constexpr int NW = D / FK::FPW;                      // words per key row
+  constexpr int WPGK = G / FK::FPW, WPGV = G / FV::FPW;   // words per group (key: channels; value: tokens)
+  constexpr int MPWK = FK::MPW, MPWV = FV::MPW;
+  constexpr int HALFK = 1 << (KB - 1), HALFV = 1 << (VB - 1);
   constexpr int NH = NH4 * 4;
 
   const int lane = threadIdx.x;
@@ -169,20 +169,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(16))) float qsum[NH4][NG][4];       // log2e/sqrt(d) * sum of q over each key group
   __shared__ __attribute__((aligned(16))) _Float16 pA[NH * TILE];       // probability operand table [head][word][mfma][slot]
   // the same two tables for the plane of high bits (1-bit fields, weight 4): [head][word][mfma][slot]
-  __shared__ __attribute__((aligned(16))) _Float16 qA1[HI ? NH * D : 8];
-  __shared__ __attribute__((aligned(16))) _Float16 pA1[HI ? NH * TILE : 8];
+  __shared__ __attribute__((aligned(16))) _Float16 qA1[HIK ? NH * D : 8];
+  __shared__ __attribute__((aligned(16))) _Float16 pA1[HIV ? NH * TILE : 8];
 
   // ---- per-(b, hk) base pointers
-  const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * BITS / 8);
+  const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * KB / 8);
   const __half* kscales = a.k.scales + bh * a.capacity * NG;
   const __half* kzeros = has_kz ? a.k.zeros + bh * a.capacity * NG : nullptr;
   const long long vgroups = a.capacity / G;
-  const uint8_t* vcodes = a.v.codes + bh * vgroups * D * (G * BITS / 8);
+  const uint8_t* vcodes = a.v.codes + bh * vgroups * D * (G * VB / 8);
   const __half* vscales = a.v.scales + bh * vgroups * D;
   const __half* vzeros = has_vz ? a.v.zeros + bh * vgroups * D : nullptr;
   const int last_row = n_both - 1, last_group = n_both / G - 1;
-  constexpr int ROWB = D * BITS / 8;                   // bytes of one key row
-  constexpr int GB = G * BITS / 8;                     // bytes of one channel of one value group
+  constexpr int ROWB = D * KB / 8;                     // bytes of one key row
+  constexpr int GB = G * VB / 8;                       // bytes of one channel of one value group
 
   // All offsets inside one (b, hk) slab fit 32 bits; bases are wave-uniform.
   auto load_tile = [&](int tile, Regs& t) {
@@ -255,11 +255,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (a.q_scale) qv = __half2float(__float2half_rn(qv * a.q_scale[hk * D + c0 + e]));
       part += qv;
       const int c = c0 + e;
-      const int word = c / F::FPW, ep = c % F::FPW;
-      const int f = ep % F::HALF;
-      const float factor = (float)(1 << (4 + LB * 4)) / (float)(1 << (LB * F::pos(f) + LB * 4));   // 2^(4 - b*pos)
-      qA[(h * NW + word) * (MPW * 4) + F::slot(ep)] = (_Float16)(qv * factor);
-      if constexpr (HI) {
+      const int word = c / FK::FPW, ep = c % FK::FPW;
+      const int f = ep % FK::HALF;
+      const float factor = (float)(1 << (4 + LBK * 4)) / (float)(1 << (LBK * FK::pos(f) + LBK * 4));   // 2^(4 - b*pos)
+      qA[(h * NW + word) * (MPWK * 4) + FK::slot(ep)] = (_Float16)(qv * factor);
+      if constexpr (HIK) {
         // 1-bit field at position pos of its half: 2^(pos - 24); weight 4 -> q * 2^(6 - pos)
         const int word1 = c / 32, ep1 = c % 32;
         const float factor1 = 64.0f / (float)(1 << F1::pos(ep1 % 16));
@@ -281,15 +281,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // reduction and no rescale.  Probabilities are then at most 2^kSlack, times the position
   // factor 2^8: still inside fp16.  l_run and o are kept divided by 2^16 (the raw MFMA scale).
   // The first tile sets the level to its exact maximum.
-  constexpr float kSlack = HI ? 5.0f : 6.0f;           // (the high-bit plane's factors reach 2^10)
+  constexpr float kSlack = HIV ? 5.0f : 6.0f;           // (the high-bit plane's factors reach 2^10)
   float m_run[NH], l_run[NH], o[NH][2];
 #pragma unroll
   for (int h = 0; h < NH; ++h) { m_run[h] = 0.f; l_run[h] = 0.f; o[h][0] = 0.f; o[h][1] = 0.f; }
 
   // where this lane's token sits in the probability operand table, and its position factor
-  const int p_e = lane % F::FPW;
-  const int p_index = (lane / F::FPW) * (MPW * 4) + F::slot(p_e);
-  const float p_shift = (float)(8 - LB * F::pos(p_e % F::HALF));        // p is stored as p * 2^(8 - b*pos)
+  const int p_e = lane % FV::FPW;
+  const int p_index = (lane / FV::FPW) * (MPWV * 4) + FV::slot(p_e);
+  const float p_shift = (float)(8 - LBV * FV::pos(p_e % FV::HALF));        // p is stored as p * 2^(8 - b*pos)
   // the same token in the high-bit plane's table: p * 4 * 2^(8 - pos), as a factor on the stored p
   const int p1_e = lane % 32;
   const int p1_index = (lane / 32) * (F1::MPW * 4) + F1::slot(p1_e);
@@ -306,29 +306,29 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int n = 0; n < NH4; ++n) acc[g][n] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int wd = 0; wd < WPG; ++wd) {
+    for (int wd = 0; wd < WPGK; ++wd) {
       uint32_t w[NG], wsft[NG];
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        const int word = g * WPG + wd;
+        const int word = g * WPGK + wd;
         w[g] = cur.k_word(word);
-        wsft[g] = w[g] >> F::SH;
+        wsft[g] = w[g] >> FK::SH;
       }
 #pragma unroll
-      for (int m = 0; m < MPW; ++m) {
+      for (int m = 0; m < MPWK; ++m) {
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
-          const int word = g * WPG + wd;
-          const half4_t bop = operand<LB>(w[g], wsft[g], m);
+          const int word = g * WPGK + wd;
+          const half4_t bop = operand<LBK>(w[g], wsft[g], m);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
-            const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPW + m) * 4]);
+            const half4_t aop = *reinterpret_cast<const half4_t*>(&qA[n * 4 * D + qa_lane + (word * MPWK + m) * 4]);
             acc[g][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, acc[g][n], 0, 0, 0);
           }
         }
       }
     }
-    if constexpr (HI) {
+    if constexpr (HIK) {
       // the plane of high bits joins the same chains: its query table carries the weight 4
 #pragma unroll
       for (int j = 0; j < HWG; ++j) {
@@ -370,9 +370,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if constexpr (has_kz) {
         const uint32_t mpair = __builtin_bit_cast(
             uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
-        zeff = __builtin_fmaf((float)half_of(mpair, g & 1), (float)(-HALFCODE), (float)half_of(cur.kz[g / 2], g & 1));
+        zeff = __builtin_fmaf((float)half_of(mpair, g & 1), (float)(-HALFK), (float)half_of(cur.kz[g / 2], g & 1));
       } else {
-        zeff = (float)s16 * (float)(-HALFCODE);
+        zeff = (float)s16 * (float)(-HALFK);
       }
       const float S = __builtin_fabsf((float)s16);
 #pragma unroll
@@ -416,7 +416,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int h = 0; h < NH; ++h) {
       const float p = __builtin_amdgcn_exp2f(e[h]);
       pA[h * TILE + p_index] = (_Float16)p;
-      if constexpr (HI) pA1[h * TILE + p1_index] = (_Float16)(p * p1_factor);
+      if constexpr (HIV) pA1[h * TILE + p1_index] = (_Float16)(p * p1_factor);
     }
     __syncthreads();
 
@@ -431,25 +431,25 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         accl[n] = acc0[n];
       }
 #pragma unroll
-      for (int wd = 0; wd < WPG; ++wd) {
+      for (int wd = 0; wd < WPGV; ++wd) {
         const uint32_t wa = cur.v_word(gi, 0, wd), wb = cur.v_word(gi, 1, wd);
-        const uint32_t was = wa >> F::SH, wbs = wb >> F::SH;
+        const uint32_t was = wa >> FV::SH, wbs = wb >> FV::SH;
 #pragma unroll
-        for (int m = 0; m < MPW; ++m) {
-          const half4_t b0 = operand<LB>(wa, was, m);
-          const half4_t b1 = operand<LB>(wb, wbs, m);
-          const half4_t b1s = ones_operand<LB>(m);
+        for (int m = 0; m < MPWV; ++m) {
+          const half4_t b0 = operand<LBV>(wa, was, m);
+          const half4_t b1 = operand<LBV>(wb, wbs, m);
+          const half4_t b1s = ones_operand<LBV>(m);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
             const half4_t aop =
-                *reinterpret_cast<const half4_t*>(&pA[n * 4 * TILE + pa_lane + ((gi * WPG + wd) * MPW + m) * 4]);
+                *reinterpret_cast<const half4_t*>(&pA[n * 4 * TILE + pa_lane + ((gi * WPGV + wd) * MPWV + m) * 4]);
             acc0[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b0, acc0[n], 0, 0, 0);
             acc1[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1, acc1[n], 0, 0, 0);
             accl[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, b1s, accl[n], 0, 0, 0);
           }
         }
       }
-      if constexpr (HI) {
+      if constexpr (HIV) {
 #pragma unroll
         for (int j = 0; j < HWG; ++j) {
           const uint32_t wa = cur.v_high(gi, 0, j), wb = cur.v_high(gi, 1, j);
@@ -474,11 +474,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if constexpr (has_vz) {
         const uint32_t mpair = __builtin_bit_cast(
             uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
-        z0 = __builtin_fmaf((float)half_of(mpair, 0), (float)(-HALFCODE), (float)half_of(cur.vz[gi], 0));
-        z1 = __builtin_fmaf((float)half_of(mpair, 1), (float)(-HALFCODE), (float)half_of(cur.vz[gi], 1));
+        z0 = __builtin_fmaf((float)half_of(mpair, 0), (float)(-HALFV), (float)half_of(cur.vz[gi], 0));
+        z1 = __builtin_fmaf((float)half_of(mpair, 1), (float)(-HALFV), (float)half_of(cur.vz[gi], 1));
       } else {
-        z0 = S0 * (float)(-HALFCODE);
-        z1 = S1 * (float)(-HALFCODE);
+        z0 = S0 * (float)(-HALFV);
+        z1 = S1 * (float)(-HALFV);
       }
       // accl = 2^-16 * (sum of the fp16 probabilities of this group); l and o stay in that scale
 #pragma unroll
@@ -543,7 +543,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ---- the window chunk of this wavefront, with a partial slot of its own
   if (s_idx < win.n_chunks) {
     __syncthreads();
-    window_pass<NH4, BITS, G, true, false>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
+    window_pass<NH4, KB, G, true, false>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
   }
 }
 
@@ -558,7 +558,7 @@ int window_cost() {
   return v;
 }
 
-template <int BITS, int G, bool ZK, bool ZV>
+template <int KB, int VB, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // A window chunk costs its wavefront about as much time as kWindowCost tiles: the wavefronts
@@ -570,79 +570,103 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   if (n_splits <= win.n_chunks) return hipErrorInvalidValue;      // the host gives at least one plain wavefront
   dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
   if (r <= 4)
-    hipExtLaunchKernelGGL((attention_inner_kernel<BITS, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+    hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
                           L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
   else
-    hipExtLaunchKernelGGL((attention_inner_kernel<BITS, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+    hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
                           L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
   return hipGetLastError();
 }
 
 // Wavefronts of this kernel instance that one compute unit holds at once (a host-side query).
-template <int BITS, int G, bool ZK, bool ZV>
+template <int KB, int VB, int G, bool ZK, bool ZV>
 int resident_z(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   int n = 0;
   hipError_t e = r <= 4
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<BITS, G, 1, ZK, ZV>, 64, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<BITS, G, 2, ZK, ZV>, 64, 0);
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<KB, VB, G, 1, ZK, ZV>, 64, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_inner_kernel<KB, VB, G, 2, ZK, ZV>, 64, 0);
   return (e == hipSuccess && n > 0) ? n : 8;
 }
 
-template <int BITS, int G>
+template <int KB, int VB, int G>
 hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return launch_z<BITS, G, true, true>(a, n_both, n_splits, win, L);
-  if (zk) return launch_z<BITS, G, true, false>(a, n_both, n_splits, win, L);
-  if (zv) return launch_z<BITS, G, false, true>(a, n_both, n_splits, win, L);
-  return launch_z<BITS, G, false, false>(a, n_both, n_splits, win, L);
+  if (zk && zv) return launch_z<KB, VB, G, true, true>(a, n_both, n_splits, win, L);
+  if (zk) return launch_z<KB, VB, G, true, false>(a, n_both, n_splits, win, L);
+  if (zv) return launch_z<KB, VB, G, false, true>(a, n_both, n_splits, win, L);
+  return launch_z<KB, VB, G, false, false>(a, n_both, n_splits, win, L);
 }
 
-template <int BITS, int G>
+template <int KB, int VB, int G>
 int resident_t(const AttnArgs& a) {
   const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return resident_z<BITS, G, true, true>(a);
-  if (zk) return resident_z<BITS, G, true, false>(a);
-  if (zv) return resident_z<BITS, G, false, true>(a);
-  return resident_z<BITS, G, false, false>(a);
+  if (zk && zv) return resident_z<KB, VB, G, true, true>(a);
+  if (zk) return resident_z<KB, VB, G, true, false>(a);
+  if (zv) return resident_z<KB, VB, G, false, true>(a);
+  return resident_z<KB, VB, G, false, false>(a);
 }
 
 }  // namespace
 
+// Width pairs (keys, values) the fused kernel is built for: equal widths, and the paper's
+// Hybrid / Small presets (3-bit keys, 2-bit values).
+inline int width_pair(const AttnArgs& a) {
+  if (a.bits == a.v_bits && a.bits >= 2 && a.bits <= 4) return a.bits - 2;   // 0, 1, 2
+  if (a.bits == 3 && a.v_bits == 2) return 3;
+  return -1;
+}
+
 bool attention_inner_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
-  return a.k.form == kPerToken && a.v.form == kPerChannel && (a.bits >= 2 && a.bits <= 4) && r <= 8 &&
-         a.capacity * D <= (1LL << 31);
+  return a.k.form == kPerToken && a.v.form == kPerChannel && width_pair(a) >= 0 && r <= 8 &&
+         (a.group == 32 || a.group == 64) && a.capacity * D <= (1LL << 31);
 }
 
-int attention_inner_waves_per_cu(const AttnArgs& a) {
-  // cached per (bits, group, zero flags, head tile): the answer depends on the kernel instance only
-  static int cache[3][2][2][2][2] = {};
-  const int r = a.n_q_heads / a.n_kv_heads;
-  int& c = cache[a.bits - 2][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
-  if (c == 0) {
-    if (a.bits == 2 && a.group == 32) c = resident_t<2, 32>(a);
-    else if (a.bits == 2 && a.group == 64) c = resident_t<2, 64>(a);
-    else if (a.bits == 3 && a.group == 32) c = resident_t<3, 32>(a);
-    else if (a.bits == 3 && a.group == 64) c = resident_t<3, 64>(a);
-    else if (a.bits == 4 && a.group == 32) c = resident_t<4, 32>(a);
-    else c = resident_t<4, 64>(a);
+// Calls f.template operator()<KB, VB, G>() for the configuration's widths and group size.
+template <typename Fn>
+auto for_widths(const AttnArgs& a, Fn f) {
+  const int wp = width_pair(a);
+  if (a.group == 32) {
+    if (wp == 0) return f.template operator()<2, 2, 32>();
+    if (wp == 1) return f.template operator()<3, 3, 32>();
+    if (wp == 2) return f.template operator()<4, 4, 32>();
+    return f.template operator()<3, 2, 32>();
   }
+  if (wp == 0) return f.template operator()<2, 2, 64>();
+  if (wp == 1) return f.template operator()<3, 3, 64>();
+  if (wp == 2) return f.template operator()<4, 4, 64>();
+  return f.template operator()<3, 2, 64>();
+}
+
+struct ResidentFn {
+  const AttnArgs& a;
+  template <int KB, int VB, int G>
+  int operator()() const { return resident_t<KB, VB, G>(a); }
+};
+struct LaunchFn {
+  const AttnArgs& a; int n_both, n_splits; const WindowSet& win; const Launch& L;
+  template <int KB, int VB, int G>
+  hipError_t operator()() const { return launch_t<KB, VB, G>(a, n_both, n_splits, win, L); }
+};
+
+int attention_inner_waves_per_cu(const AttnArgs& a) {
+  // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
+  static int cache[4][2][2][2][2] = {};
+  const int r = a.n_q_heads / a.n_kv_heads;
+  const int wp = width_pair(a);
+  if (wp < 0) return 8;
+  int& c = cache[wp][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
+  if (c == 0) c = for_widths(a, ResidentFn{a});
   return c;
 }
 
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  const int n_both = (int)n_both_ll;
+  if (!attention_inner_supported(a)) return hipErrorInvalidValue;
   const Launch L = {stream, ev_start, ev_stop};
-  if (a.bits == 2 && a.group == 32) return launch_t<2, 32>(a, n_both, n_splits, win, L);
-  if (a.bits == 2 && a.group == 64) return launch_t<2, 64>(a, n_both, n_splits, win, L);
-  if (a.bits == 4 && a.group == 32) return launch_t<4, 32>(a, n_both, n_splits, win, L);
-  if (a.bits == 4 && a.group == 64) return launch_t<4, 64>(a, n_both, n_splits, win, L);
-  if (a.bits == 3 && a.group == 32) return launch_t<3, 32>(a, n_both, n_splits, win, L);
-  if (a.bits == 3 && a.group == 64) return launch_t<3, 64>(a, n_both, n_splits, win, L);
-  return hipErrorInvalidValue;
+  return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});
 }
 
 }  // namespace innerq

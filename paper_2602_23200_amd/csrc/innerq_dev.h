@@ -32,12 +32,15 @@ struct TensorView {
   const __half* sink;
   const __half* ring;
   int form;            // Form
+  int bits;            // code width of this tensor
   int slots;           // ring slots
   int n_sink;          // tokens currently in the sink window
   long long n_quant;   // tokens currently in the quantised store
 };
 
 struct Partition { long long n_sink, n_quant, n_recent; };
+
+inline int bits_of(const innerq_config_t& c, int which) { return (which == 1 && c.v_bits) ? c.v_bits : c.bits; }
 
 inline Partition partition_of(const innerq_config_t& c, int which, long long n) {
   Partition p;
@@ -62,7 +65,7 @@ struct QuantTensorJob {
   // destination store
   uint8_t* codes; __half* scales; __half* zeros; __half* sink; __half* ring;
   const __half* x_new;       // [B][Hk][t_new][d]
-  int form, mode, slots;
+  int form, mode, slots, bits;
   long long row_begin, row_end;   // store rows to quantise in this call (token = w_sink + row)
   long long ring_from;            // new tokens with index >= ring_from go to the ring
   int normalise;                  // apply k_inv_norm to tokens taken from x_new
@@ -71,7 +74,7 @@ struct QuantTensorJob {
 struct QuantArgs {
   QuantTensorJob job[2];          // K, V
   const float* inv_norm;          // [Hk][d] or null
-  int batch, n_kv_heads, bits, group, w_sink, sym_den_literal;
+  int batch, n_kv_heads, group, w_sink, sym_den_literal;
   long long capacity, n_old, t_new;
 };
 
@@ -87,7 +90,7 @@ struct AttnArgs {
   float* ws_ml;             // [B*Hq][n_partials][2]
   float* ws_o;              // [B*Hq][n_partials][d]
   int n_partials;           // partial slots per head in this launch
-  int batch, n_q_heads, n_kv_heads, bits, group, w_sink;
+  int batch, n_q_heads, n_kv_heads, bits, v_bits, group, w_sink;   // bits: key codes, v_bits: value codes
   long long capacity, n_tokens;
 };
 

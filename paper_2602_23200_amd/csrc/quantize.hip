@@ -195,17 +195,9 @@ __global__ void __launch_bounds__(256) window_copy_kernel(QuantArgs a) {
   window_copy(a, a.job[blockIdx.y], (long long)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
+// The quantise work of thread idx of tensor job j (keys and values may have different widths).
 template <int G, int BITS>
-__global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long copy_from) {
-  // Thread indices below copy_from quantise evicted tokens, those from copy_from on write the
-  // new tokens into the windows (one launch; only used when no new token lands in a ring slot
-  // that this call still has to read).  copy_from < 0: no copy work in this launch.
-  const QuantTensorJob& j = a.job[blockIdx.y];
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (copy_from >= 0 && idx >= copy_from) {
-    window_copy(a, j, idx - copy_from);
-    return;
-  }
+__device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
   const long long n_rows = j.row_end - j.row_begin;
   if (n_rows <= 0) return;
   const long long BH = (long long)a.batch * a.n_kv_heads;
@@ -302,7 +294,23 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
   }
 }
 
-template <int G, int BITS>
+template <int G>
+__global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long copy_from) {
+  // Thread indices below copy_from quantise evicted tokens, those from copy_from on write the
+  // new tokens into the windows (one launch; only used when no new token lands in a ring slot
+  // that this call still has to read).  copy_from < 0: no copy work in this launch.
+  const QuantTensorJob& j = a.job[blockIdx.y];
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (copy_from >= 0 && idx >= copy_from) {
+    window_copy(a, j, idx - copy_from);
+    return;
+  }
+  if (j.bits == 2) quantize_rows<G, 2>(a, j, idx);
+  else if (j.bits == 3) quantize_rows<G, 3>(a, j, idx);
+  else quantize_rows<G, 4>(a, j, idx);
+}
+
+template <int G>
 hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
   const long long BH = (long long)a.batch * a.n_kv_heads;
   long long threads = 0;
@@ -330,12 +338,12 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
   if (threads > 0 && disjoint) {
     const long long qthreads = ((threads + 255) / 256) * 256;
     dim3 grid((unsigned)((qthreads + cthreads + 255) / 256), 2);
-    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a, qthreads);
+    quantize_kernel<G><<<grid, 256, 0, stream>>>(a, qthreads);
     return hipGetLastError();
   }
   if (threads > 0) {
     dim3 grid((unsigned)((threads + 255) / 256), 2);
-    quantize_kernel<G, BITS><<<grid, 256, 0, stream>>>(a, -1);
+    quantize_kernel<G><<<grid, 256, 0, stream>>>(a, -1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -402,12 +410,10 @@ __global__ void norm_finalize_kernel(uint32_t* table, int n_kv_heads, int per_he
 }  // namespace
 
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream) {
-  if (a.bits == 2 && a.group == 32) return launch_quantize_t<32, 2>(a, stream);
-  if (a.bits == 2 && a.group == 64) return launch_quantize_t<64, 2>(a, stream);
-  if (a.bits == 4 && a.group == 32) return launch_quantize_t<32, 4>(a, stream);
-  if (a.bits == 4 && a.group == 64) return launch_quantize_t<64, 4>(a, stream);
-  if (a.bits == 3 && a.group == 32) return launch_quantize_t<32, 3>(a, stream);
-  if (a.bits == 3 && a.group == 64) return launch_quantize_t<64, 3>(a, stream);
+  for (int w = 0; w < 2; ++w)
+    if (a.job[w].form != kFp16 && (a.job[w].bits < 2 || a.job[w].bits > 4)) return hipErrorInvalidValue;
+  if (a.group == 32) return launch_quantize_t<32>(a, stream);
+  if (a.group == 64) return launch_quantize_t<64>(a, stream);
   return hipErrorInvalidValue;
 }
 

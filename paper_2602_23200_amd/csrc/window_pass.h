@@ -21,7 +21,7 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
   const long long row = t - a.w_sink;
   if (row >= tv.n_quant) return __half2float(tv.ring[(bh * tv.slots + (t % tv.slots)) * D + c]);
   if (tv.form == kFp16) return __half2float(reinterpret_cast<const __half*>(tv.codes)[(bh * a.capacity + row) * D + c]);
-  const int bits = a.bits, G = a.group;
+  const int bits = tv.bits, G = a.group;
   long long si;
   unsigned field;
   // field i of a packed run of n fields that starts at byte address p (3-bit: a plane of 2-bit

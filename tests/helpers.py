@@ -31,7 +31,8 @@ def bits_view(a: np.ndarray) -> np.ndarray:
 def gpu_config(o: orc.Config):
     from paper_2602_23200_amd import binding as iq
     return iq.make_config(o.batch, o.n_q_heads, o.n_kv_heads, o.head_dim, o.bits, o.group, o.w_sink,
-                          o.w_recent, o.k_mode, o.v_mode, o.sym_denominator, o.kind, o.capacity_tokens)
+                          o.w_recent, o.k_mode, o.v_mode, o.sym_denominator, o.kind, o.capacity_tokens,
+                          o.v_bits)
 
 
 def gpu_buffer_as_numpy(gcache, o: orc.Config, name: str):

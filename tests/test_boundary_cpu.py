@@ -42,7 +42,9 @@ def cfg_of(w, kind=iq.KIND_INNER, **over):
 
 
 def test_struct_layout_matches_header_order():
-    assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8
+    # twelve int32, one int64, one int32 (+ tail padding to the int64 alignment)
+    assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8 + 8
+    assert iq.innerq_config_t.capacity_tokens.offset == 48 and iq.innerq_config_t.v_bits.offset == 56
     assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8
 
 
@@ -57,6 +59,8 @@ def test_validate_config_rejections():
         (dict(bits=5), iq.E_UNSUPPORTED),            # only 2, 3 and 4 bits are built
         (dict(bits=8), iq.E_UNSUPPORTED),
         (dict(bits=0), iq.E_ARG),
+        (dict(v_bits=5), iq.E_UNSUPPORTED),
+        (dict(v_bits=-1), iq.E_ARG),
         (dict(head_dim=64, group=32), iq.E_UNSUPPORTED),
         (dict(w_recent=0), iq.E_ARG),
         (dict(w_sink=-1), iq.E_ARG),
@@ -79,8 +83,10 @@ def test_validate_config_rejections():
 @pytest.mark.parametrize("name", ["tiny", "llama3_8b_32k", "mistral_7b_8k"])
 def test_buffer_bytes_match_oracle_buffers(kind, name):
     w = wl.WORKLOADS[name].with_(batch=1, n_tokens=512)
-    for mode in (iq.SYM, iq.HYBRID):
-        c, o = cfg_of(w.with_(k_mode=mode, v_mode=mode), kind=kind)
+    for mode, bits, v_bits in ((iq.SYM, w.bits, 0), (iq.HYBRID, w.bits, 0), (iq.HYBRID, 3, 0), (iq.SYM, 3, 2),
+                               (iq.HYBRID, 2, 4)):
+        c, o = cfg_of(w.with_(k_mode=mode, v_mode=mode, bits=bits), kind=kind, v_bits=v_bits)
+        o.v_bits = v_bits
         cache = orc.cache_new(o)
         for i, f in enumerate(iq.BUFFER_NAMES):
             a = getattr(cache, f)

@@ -308,3 +308,35 @@ def test_crafted_flag_density_cache(env, frac):
     torch.cuda.synchronize()
     ref = orc.decode_attention(o, want, q, None)
     assert max_rel_err(out.cpu().numpy(), ref) <= TOL
+
+
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
+@pytest.mark.parametrize("k_bits,v_bits,group,k_mode,v_mode", [
+    (3, 2, 32, orc.SYM, orc.HYBRID),      # the paper's Hybrid preset
+    (3, 2, 32, orc.SYM, orc.SYM),         # Small
+    (3, 3, 32, orc.SYM, orc.SYM),         # Base
+    (3, 2, 64, orc.HYBRID, orc.HYBRID),
+    (2, 4, 32, orc.HYBRID, orc.ASYM),     # a pair the fused kernel is not built for: generic path
+])
+def test_separate_key_and_value_widths(env, kind, k_bits, v_bits, group, k_mode, v_mode):
+    """Caches whose keys and values have different code widths: stores bit-exact, attention within
+    tolerance, after a bulk append followed by single-token appends (so that both quantiser
+    paths and a value spill run at both widths)."""
+    torch, iq = env
+    w = small(bits=k_bits, group=group, k_mode=k_mode, v_mode=v_mode, n_tokens=900)
+    o = oracle_config(w, kind=kind, v_bits=v_bits)
+    K, V = wl.kv_full(w)
+    n0 = 900 - 70
+    want = orc.cache_init_prefill(o, K[:, :, :n0], V[:, :, :n0])
+    orc.quantize_append(o, want, K[:, :, n0:], V[:, :, n0:])
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K[:, :, :n0]), to_dev(torch, V[:, :, :n0]))
+    for t in range(n0, 900):
+        iq.innerq_quantize_append(g, to_dev(torch, K[:, :, t:t + 1]), to_dev(torch, V[:, :, t:t + 1]))
+    torch.cuda.synchronize()
+    assert_cache_equal(g, want, o, what=f"kind{kind} k{k_bits} v{v_bits} G{group}")
+    q = wl.query(w)
+    out = iq.innerq_decode_attention(g, to_dev(torch, q), iq.allocate_workspace(g.cfg))
+    torch.cuda.synchronize()
+    ref = orc.decode_attention(o, want, q)
+    assert max_rel_err(out.cpu().numpy(), ref) <= TOL
