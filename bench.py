@@ -305,6 +305,23 @@ def main():
     per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
     alg_bytes = per_unit * units
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+
+    # yardstick: a plain streaming read of the same number of bytes (rotating buffers, so the
+    # last-level cache does not help), timed the same way
+    n_buf = max(2, min(8, (1 << 31) // max(alg_bytes, 1)))
+    probe_bytes = (alg_bytes // 16) * 16
+    bufs = [torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(n_buf)]
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    ev0, ev1 = evs[0][0]
+    probe_ms = []
+    for i in range(40):
+        iq.innerq_stream_read_probe(bufs[i % n_buf], sink, ev0, ev1, stream=stream)
+        torch.cuda.synchronize()
+        if i >= 8:
+            probe_ms.append(hip.elapsed_ms(ev0, ev1))
+    del bufs
+    stream_gbs = probe_bytes / (sum(probe_ms) / len(probe_ms) * 1e-3) / 1e9
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (a recorded figure:
     # counters cannot be read from inside this process); null if this workload was not profiled
     traffic = None
@@ -338,7 +355,10 @@ def main():
                      "kernel": "fused dequant score+value pass over the quantised range",
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_ms_median,
                      "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_token_kvhead": per_unit,
-                     "token_kvheads_per_launch": units},
+                     "token_kvheads_per_launch": units,
+                     "streaming_read_same_bytes": {"achieved": stream_gbs, "unit": "GB/s",
+                                                   "frac_of_peak": stream_gbs / HBM_PEAK_GBS,
+                                                   "kernel_frac_of_it": achieved / stream_gbs}},
         "breakdown_ms": {"step": ms_per_step, "step_with_events": (t3 - t2) / K * 1e3,
                          "attention_only": attn_ms, "append_only": append_ms},
     }

@@ -198,6 +198,16 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
  * cancels a pending request. */
 int innerq_profile_next_attention(void *ev_start, void *ev_stop);
 
+/* Measurement yardstick (no counterpart in the paper): a plain read-only streaming kernel
+ * over `bytes` bytes of device memory at `data` (16-byte aligned, bytes a multiple of 16),
+ * launched on hip_stream.  It gives the rate a pure HBM read of that size reaches on this
+ * device, launch and ramp included, to set beside the fused kernel's rate over the same
+ * number of bytes.  `sink` is 4 bytes of writable device memory (written practically never;
+ * it keeps the loads alive).  ev_start / ev_stop (hipEvent_t, may be NULL) take the begin and
+ * end timestamps of the dispatch.  Returns INNERQ_E_NULL / _ALIGN / _ARG before any launch. */
+int innerq_stream_read_probe(const void *data, size_t bytes, void *sink, void *hip_stream,
+                             void *ev_start, void *ev_stop);
+
 #ifdef __cplusplus
 }
 #endif

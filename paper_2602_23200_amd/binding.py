@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.innerq_decode_attention.restype = C.c_int
         L.innerq_profile_next_attention.argtypes = [C.c_void_p, C.c_void_p]
         L.innerq_profile_next_attention.restype = C.c_int
+        L.innerq_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.innerq_stream_read_probe.restype = C.c_int
         _lib = L
     return _lib
 
@@ -198,3 +200,12 @@ def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, 
 def innerq_profile_next_attention(ev_start: Optional[int], ev_stop: Optional[int]) -> None:
     """ev_start / ev_stop: raw hipEvent_t handles (ints), or None to cancel."""
     lib().innerq_profile_next_attention(ev_start, ev_stop)
+
+
+def innerq_stream_read_probe(data, sink, ev_start: Optional[int] = None, ev_stop: Optional[int] = None,
+                             stream=None) -> None:
+    """Plain streaming read of the CUDA tensor `data` (byte count a multiple of 16); `sink`: >= 4 bytes."""
+    st = lib().innerq_stream_read_probe(data.data_ptr(), data.numel() * data.element_size(), sink.data_ptr(),
+                                        _stream(stream), ev_start, ev_stop)
+    if st != OK:
+        raise InnerQError(st, "innerq_stream_read_probe")

@@ -17,6 +17,7 @@ SOURCES = {
     "api.hip": [],
     "quantize.hip": ["-ffp-contract=off"],
     "attention_generic.hip": [],
+    "stream_probe.hip": [],
     "attention_fp16.hip": ["-fno-honor-nans"],
     "attention_outer.hip": ["-fno-honor-nans"],
     # no NaN canonicalisation around fmax; MFMA results straight into VGPRs

@@ -323,4 +323,19 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
 }
 
+int innerq_stream_read_probe(const void* data, size_t bytes, void* sink, void* hip_stream, void* ev_start,
+                             void* ev_stop) {
+  if (!data || !sink) return INNERQ_E_NULL;
+  if (misaligned(data) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return INNERQ_E_ALIGN;
+  if (bytes == 0 || bytes % 16 != 0) return INNERQ_E_ARG;
+  // as many resident work-groups as the device holds (8 of 256 lanes per compute unit), fewer for small sizes
+  long long blocks = (long long)compute_units() * 8;
+  const long long needed = (long long)((bytes / 16 + 1023) / 1024);
+  if (blocks > needed) blocks = needed;
+  const hipError_t e = launch_stream_read(data, bytes, static_cast<uint32_t*>(sink), (int)blocks,
+                                          static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_start),
+                                          static_cast<hipEvent_t>(ev_stop));
+  return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
+}
+
 }  // extern "C"

@@ -127,4 +127,9 @@ int attention_outer_waves_per_cu(const AttnArgs& a);
 hipError_t launch_attention_outer(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
+// Plain streaming read of `bytes` bytes (a multiple of 16) by n_blocks work-groups of 256 lanes;
+// `sink` is 4 writable bytes.
+hipError_t launch_stream_read(const void* data, size_t bytes, uint32_t* sink, int n_blocks, hipStream_t stream,
+                              hipEvent_t ev_start, hipEvent_t ev_stop);
+
 }  // namespace innerq
