@@ -24,9 +24,17 @@
 //     place inside a 16-bit half it is the fp16 denormal u * 2^(b*pos) * 2^-24
 //     (the matrix cores keep fp16 denormals); the position factor is folded into
 //     the A operand (query / probabilities), the constant into the group scale.
+//   * 3-bit fields are stored as a plane of 2-bit low parts followed by a plane of
+//     high bits; the high bits are 1-bit fields of the same kind (2^(pos - 24)) and
+//     join the same MFMA chains through operand tables that carry their weight 4.
+//     Keys and values may have different widths (template parameters KB, VB).
 //   * softmax probabilities are rounded to fp16 for the value pass and the
 //     normaliser is the MFMA sum of those same rounded values (an extra all-ones B
 //     operand), so the weights stay consistent.
+//   * schedule: n_splits + n_window_chunks wavefronts per (batch, kv-head), all
+//     resident at once at two per SIMD; contiguous tile ranges; two register
+//     buffers in ping-pong; the wavefront that is behind its SIMD partner gets the
+//     higher issue priority, so both finish together.
 #include "innerq_dev.h"
 #include "window_pass.h"
 
