@@ -11,8 +11,9 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 
 inline long long ceil_div(long long a, long long b) { return (a + b - 1) / b; }
 
+// Most window chunks a launch may use (chunks of kWindowChunkMin tokens); bounds the workspace.
 inline int window_chunk_cap(const innerq_config_t& c) {
-  return (int)ceil_div((long long)c.w_sink + c.w_recent + 2LL * c.group, kWindowChunk) + 1;
+  return (int)ceil_div((long long)c.w_sink + c.w_recent + 2LL * c.group, kWindowChunkMin) + 1;
 }
 // Most token splits a launch may use for the quantised range; bounds the workspace.  Never below
 // the window chunk count plus one: the fused inner kernel needs one wavefront beyond those that
@@ -254,7 +255,7 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   const long long win_b0 = c.w_sink + n_both, win_b1 = N > win_b0 ? N : win_b0;
   const long long win_tokens = n_sink + (win_b1 - win_b0);
   const int r = c.n_q_heads / c.n_kv_heads;
-  int n_splits = 0;
+  int n_splits = 0, win_chunk_len = kWindowChunk;
   // which fused kernel serves this cache (0 = none: element-by-element fallback)
   const int fused_kind =
       attention_inner_supported(a) ? 1 : attention_fp16_supported(a) ? 2 : attention_outer_supported(a) ? 3 : 0;
@@ -266,22 +267,28 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
                             (fused_kind == 1   ? attention_inner_waves_per_cu(a)
                              : fused_kind == 2 ? attention_fp16_waves_per_cu(a)
                                                : attention_outer_waves_per_cu(a));
-    const long long n_win_chunks = ceil_div(win_tokens, kWindowChunk);
     const long long n_tiles = ceil_div(n_both, 64);
-    long long s = slots / ((long long)c.batch * c.n_kv_heads);
-    if (fused_kind == 1) {
-      // the inner kernel's first wavefronts each carry a window chunk besides their tiles
-      if (s > n_tiles + n_win_chunks) s = n_tiles + n_win_chunks;
-      if (s > split_cap(c)) s = split_cap(c);
-      if (s < n_win_chunks + 1) s = n_win_chunks + 1;
-    } else {
-      // the comparison kernels run the window chunks as extra wavefronts of the same launch
-      s -= n_win_chunks;
-      if (s > n_tiles) s = n_tiles;
-      if (s > split_cap(c)) s = split_cap(c);
-      if (s < 1) s = 1;
+    const long long per_head = slots / ((long long)c.batch * c.n_kv_heads);
+    // Window chunk length: 64 tokens when the wavefront slots are all needed for tiles (long
+    // contexts: a chunk then hides behind the tile work), shorter when slots are to spare and the
+    // window chunk would be the longest wavefront of the launch.  Costs in units of one tile of
+    // one wavefront: a chunk of L tokens about 4 + 14 L / 64.
+    long long best_len = kWindowChunk, best_cost = -1, best_plain = 1;
+    for (long long len = kWindowChunk; len >= kWindowChunkMin; len /= 2) {
+      const long long nw = ceil_div(win_tokens, len);
+      long long plain = per_head - nw;
+      if (plain > n_tiles) plain = n_tiles;
+      if (plain > split_cap(c)) plain = split_cap(c);
+      if (plain < 1) plain = 1;
+      const long long tile_cost = ceil_div(n_tiles, plain) * 8, win_cost = nw ? 32 + 14 * len / 8 : 0;   // x 8
+      const long long cost = tile_cost > win_cost ? tile_cost : win_cost;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_len = len; best_plain = plain; }
     }
-    n_splits = (int)s;
+    win_chunk_len = (int)best_len;
+    const long long n_win_chunks = ceil_div(win_tokens, best_len);
+    // the inner kernel's first wavefronts each carry a window chunk besides their tiles; the
+    // comparison kernels run the window chunks as extra wavefronts of the same launch
+    n_splits = (int)(fused_kind == 1 ? best_plain + n_win_chunks : best_plain);
   } else if (n_both > 0) {
     const long long blocks_per_split = (long long)c.batch * c.n_kv_heads * ceil_div(r, kHeadTile);
     long long s = ceil_div(2048, blocks_per_split);
@@ -291,7 +298,7 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
     if (s < 1) s = 1;
     n_splits = (int)s;
   }
-  const int n_win = (int)ceil_div(win_tokens, kWindowChunk);
+  const int n_win = (int)ceil_div(win_tokens, win_chunk_len);
   if (n_win > window_chunk_cap(c)) return INNERQ_E_ARG;
   a.n_partials = n_splits + n_win;
   const size_t heads = (size_t)c.batch * c.n_q_heads;

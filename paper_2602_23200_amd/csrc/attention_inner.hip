@@ -553,18 +553,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
-// Tiles' worth of wall time one 64-token window chunk takes next to a streaming partner
-// (measured: about 16 us against 1.8 us per tile, with little of the SIMD's issue slots used).
-constexpr int kWindowCost = 18;
+// Tiles' worth of wall time a window chunk of `len` tokens takes next to a streaming partner
+// (measured for 64 tokens: about 16 us against 1.8 us per tile, little of it issue slots).
+inline int window_cost(long long len) { return (int)(4 + 14 * len / 64); }
 
 template <int KB, int VB, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
-  // A window chunk costs its wavefront about as much time as kWindowCost tiles: the wavefronts
+  // A window chunk costs its wavefront about as much time as window_cost() tiles: the wavefronts
   // that carry one get that many tiles fewer than the common quota.
   const int n_tiles = (n_both + TILE - 1) / TILE;
-  const int quota = (n_tiles + win.n_chunks * kWindowCost + n_splits - 1) / n_splits;
-  int win_tiles = quota > kWindowCost ? quota - kWindowCost : 0;
+  const int cost = win.n_chunks > 0 ? window_cost((win.na + win.nb + win.n_chunks - 1) / win.n_chunks) : 0;
+  const int quota = (n_tiles + win.n_chunks * cost + n_splits - 1) / n_splits;
+  int win_tiles = quota > cost ? quota - cost : 0;
   if (win.n_chunks > 0 && win_tiles > n_tiles / win.n_chunks) win_tiles = n_tiles / win.n_chunks;
   if (n_splits <= win.n_chunks) return hipErrorInvalidValue;      // the host gives at least one plain wavefront
   dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));

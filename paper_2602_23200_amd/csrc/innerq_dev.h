@@ -12,7 +12,8 @@
 namespace innerq {
 
 constexpr int kHeadDim = 128;          // the only head_dim built
-constexpr int kWindowChunk = 64;       // window tokens per wavefront / work-group chunk
+constexpr int kWindowChunk = 64;       // most window tokens per wavefront / work-group chunk
+constexpr int kWindowChunkMin = 16;    // fewest (short contexts, slots to spare)
 constexpr int kHeadTile = 4;           // query heads served by one work-group pass
 
 enum Form : int { kPerToken = 0, kPerChannel = 1, kFp16 = 2 };

@@ -163,6 +163,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     }
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
+      if (4 * k >= n_here) break;                        // (uniform) no row left in this step
       const int j = 4 * k + tg;
       const long long tj = token_of(base + (j < n_here ? j : n_here - 1));
       const __half* vrow = fp16_row(a.v, a, bh, tj);
@@ -305,6 +306,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     // lane groups are summed at the end.  Rows past the end carry probability 0.
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
+      if (4 * k >= n_here) break;                        // (uniform) no row left in this step
       const int j = 4 * k + tg;
       float x[8];
       if (VQ && ((v_packed >> k) & 1u)) {
