@@ -340,3 +340,36 @@ def test_separate_key_and_value_widths(env, kind, k_bits, v_bits, group, k_mode,
     torch.cuda.synchronize()
     ref = orc.decode_attention(o, want, q)
     assert max_rel_err(out.cpu().numpy(), ref) <= TOL
+
+
+def _random_case(i):
+    r = np.random.default_rng(1000 + i)
+    k_bits = int(r.choice([2, 3, 4]))
+    v_bits = 2 if (k_bits == 3 and i % 2 == 0) else 0
+    hk = int(r.choice([1, 2, 3]))
+    ratio = int(r.choice([1, 2, 4, 5, 8]))
+    group = int(r.choice([32, 64]))
+    w_sink = int(r.choice([0, 1, 4, 7]))
+    w_recent = int(r.choice([1, 16, 48, 130]))
+    n_tokens = int(r.integers(1, 4200))
+    modes = [orc.SYM, orc.ASYM, orc.HYBRID]
+    return dict(batch=int(r.choice([1, 2])), n_q_heads=hk * ratio, n_kv_heads=hk, bits=k_bits, group=group,
+                w_sink=w_sink, w_recent=w_recent, n_tokens=n_tokens, k_mode=modes[int(r.integers(3))],
+                v_mode=modes[int(r.integers(3))], seed=500 + i), v_bits
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_configurations(env, i):
+    """Seeded random shapes, widths, modes, windows and lengths (ragged tiles, windows longer than
+    the context, 1 to 8 query heads per kv head): cache bit-exact, attention within tolerance."""
+    torch, iq = env
+    kw, v_bits = _random_case(i)
+    w = small(**kw)
+    o = oracle_config(w, v_bits=v_bits)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want_cache = orc.cache_init_prefill(o, K, V)
+    want = orc.decode_attention(o, want_cache, q)
+    g, got = run_attention(torch, iq, o, K, V, q)
+    assert_cache_equal(g, want_cache, o, what=str(kw))
+    assert max_rel_err(got, want) <= TOL, (kw, v_bits)
