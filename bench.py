@@ -46,6 +46,9 @@ def parse():
                    help="fill the caches with crafted groups of which a fraction F is quantised asymmetrically "
                         "in hybrid mode (the rest symmetrically): the density sweep of the flag matrix "
                         "(paper, Section 'Sparsity of M')")
+    p.add_argument("--prefill", action="store_true",
+                   help="time the prefill-side calls instead (key-norm calibration and the bulk append that "
+                        "quantises a whole prompt) and print their rates; exits without the decode loop")
     p.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                    help="run only a plain elementwise copy of MIB mebibytes, 10 times (reference for the "
                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters), and exit")
@@ -140,6 +143,36 @@ def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None):
     return cache
 
 
+def prefill_rates(torch, iq, w, cfg, gen):
+    """Prefill-side calls on one prompt of the workload's length: calibration reads the fp16 keys
+    once; the bulk append reads fp16 keys and values once and writes the packed cache."""
+    B, Hk, d, N = w.batch, w.n_kv_heads, w.head_dim, w.n_tokens
+    k = torch.randn((B, Hk, N, d), device="cuda", generator=gen).half()
+    v = torch.randn((B, Hk, N, d), device="cuda", generator=gen).half()
+    fp16_bytes = k.numel() * 2
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    timed(lambda: iq.innerq_calibrate_key_norm(cfg, k), 2)
+    t_cal = timed(lambda: iq.innerq_calibrate_key_norm(cfg, k), 10)
+    caches = [iq.allocate_cache(cfg) for _ in range(3)]
+    iq.innerq_quantize_append(caches[0], k, v)
+    t_app = timed(lambda c=iter(caches[1:]): iq.innerq_quantize_append(next(c), k, v), 2)
+    written = sum(b.numel() for b in caches[1].buffers.values() if b is not None)
+    print(json.dumps({
+        "prefill": True, "workload": w.name, "tokens": N, "batch": B,
+        "calibrate_key_norm": {"ms": t_cal * 1e3, "read_GBps": fp16_bytes / t_cal / 1e9},
+        "bulk_quantize_append": {"ms": t_app * 1e3, "read_GBps": 2 * fp16_bytes / t_app / 1e9,
+                                 "tokens_per_s": B * N / t_app, "cache_bytes_allocated": written},
+    }))
+
+
 def cpu_baseline(w, kind_id, seconds, v_bits=0):
     """The CPU oracle timed on a bounded sample of the same workload: whole (batch, kv-head) slabs,
     each one decode step (append one token + attention for the slab's query heads)."""
@@ -219,6 +252,9 @@ def main():
                          w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
+    if args.prefill:
+        prefill_rates(torch, iq, w, cfg, gen)
+        return
     caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen, args.asym_frac)
               for i in range(n_inst)]
     B, Hq, Hk, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim

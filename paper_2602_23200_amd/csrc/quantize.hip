@@ -68,6 +68,73 @@ __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den
   zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
 }
 
+// The same group quantiser for values that are fetched on demand (x(i) returns element i; it is
+// called twice per element: once for the range, once for the codes), so that no array of G
+// values has to live in registers.  Same operations in the same order as quantize_group.
+template <int G, int BITS, typename Fetch>
+__device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_literal,
+                                               uint32_t (&words)[G * BITS / 32], __half& scale, __half& zero) {
+  constexpr int W = G * BITS / 32;
+  constexpr int QMAX = (1 << BITS) - 1;
+  constexpr int HALF = 1 << (BITS - 1);
+  constexpr int LB = BITS == 3 ? 2 : BITS;             // field width of the (low) plane
+  constexpr int FPW = 32 / LB;                         // fields per word of it
+  const float x0 = x(0);
+  float mn = x0, mx = x0, am = fabsf(x0);
+  for (int i = 1; i < G; ++i) {
+    const float v = x(i);
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+    am = fmaxf(am, fabsf(v));
+  }
+  const float den = sym_den_literal ? (float)QMAX : (float)(HALF - 1);
+  const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
+  const __half Ss = __float2half_rn(am / den);
+  const float Saf = h2f(Sa), Ssf = h2f(Ss);
+  uint32_t wa[W], ws[W];
+#pragma unroll
+  for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
+  float ea = 0.f, es = 0.f;
+  // word by word (static indices into wa / ws), fields in index order inside each word
+#pragma unroll
+  for (int w = 0; w < G / FPW; ++w) {
+    uint32_t la = 0u, ls = 0u, ha = 0u, hs = 0u;
+    for (int f = 0; f < FPW; ++f) {
+      const int i = w * FPW + f;
+      const float v = x(i);
+      float ca = fminf(fmaxf(rintf((v - mn) / Saf), 0.f), (float)QMAX);
+      ca = (Saf == 0.f) ? 0.f : ca;
+      float cs = fminf(fmaxf(rintf(v / Ssf), (float)(-HALF)), (float)(HALF - 1));
+      cs = (Ssf == 0.f) ? 0.f : cs;
+      const float ra = Saf * ca + mn;
+      const float rs = Ssf * cs;
+      ea = ea + fabsf(v - ra);
+      es = es + fabsf(v - rs);
+      const uint32_t ua = (uint32_t)(int)ca, us = (uint32_t)((int)cs + HALF);
+      if constexpr (BITS == 3) {
+        la |= (ua & 3u) << (f * 2);
+        ls |= (us & 3u) << (f * 2);
+        ha |= (ua >> 2) << f;
+        hs |= (us >> 2) << f;
+      } else {
+        la |= ua << (f * BITS);
+        ls |= us << (f * BITS);
+      }
+    }
+    wa[w] = la;
+    ws[w] = ls;
+    if constexpr (BITS == 3) {                         // 16 high bits per low word: two low words share one
+      wa[G / 16 + w / 2] |= ha << (16 * (w % 2));
+      ws[G / 16 + w / 2] |= hs << (16 * (w % 2));
+    }
+  }
+  const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
+#pragma unroll
+  for (int i = 0; i < W; ++i) words[i] = asym ? wa[i] : ws[i];
+  scale = asym ? __hneg(Sa) : Ss;
+  zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
+}
+
 // The same group quantiser spread over 8 neighbouring lanes (lane `sub` of the group holds the
 // G/8 consecutive values x): the per-element divisions run in parallel, minimum / maximum are
 // exact in any order, and the two error sums are still taken one element after the other in
@@ -255,18 +322,25 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
     const int c = (int)(idx % kHeadDim);
     const long long tg = j.row_begin / G + (idx / kHeadDim) % n_groups;   // token-group index in the store
     const long long bh = idx / (kHeadDim * n_groups);
-    float x[G];
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
+    const float inv = j.normalise ? a.inv_norm[(bh % a.n_kv_heads) * kHeadDim + c] : 1.f;
+    auto fetch = [&](int i) -> float {
       bool from_new;
       const __half* src = token_row(j, a, bh, a.w_sink + tg * G + i, from_new);
       float v = h2f(src[c]);
-      if (from_new && j.normalise) v = h2f(__float2half_rn(v * a.inv_norm[(bh % a.n_kv_heads) * kHeadDim + c]));
-      x[i] = v;
-    }
+      if (from_new && j.normalise) v = h2f(__float2half_rn(v * inv));
+      return v;
+    };
     uint32_t words[W];
     __half s, z;
-    quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+    if constexpr (G <= 32) {
+      float x[G];
+#pragma unroll
+      for (int i = 0; i < G; ++i) x[i] = fetch(i);
+      quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+    } else {
+      // 64 values do not fit the register file next to the rest: fetch each element twice
+      quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+    }
     const long long go = (bh * (a.capacity / G) + tg) * kHeadDim + c;
     uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes) + go * W;
 #pragma unroll
