@@ -553,9 +553,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
-// Tiles' worth of wall time a window chunk of `len` tokens takes next to a streaming partner
-// (measured for 64 tokens: about 16 us against 1.8 us per tile, little of it issue slots).
-inline int window_cost(long long len) { return (int)(4 + 14 * len / 64); }
+// Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it
+// (a 64-token chunk takes about 16 us of wall time against 1.8 us per tile, but little of it is
+// issue slots; the figure that balances the launch best, swept from 4 to 18, is about 13).
+inline int window_cost(long long len) { return (int)(2 + 11 * len / 64); }
 
 template <int KB, int VB, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
