@@ -160,7 +160,9 @@ int innerq_calibrate_key_norm(const innerq_config_t *cfg, const void *k_fp16, in
  *   k_new, v_new  device, fp16 [B][Hk][t_new][d], contiguous, read only
  *   k_inv_norm    device, fp32 [Hk][d] or NULL.  When given, every new key is
  *                 replaced by fp16(float(k) * k_inv_norm[hk][c]) on its way in
- *                 (for keys produced before the factors were folded into W_K).
+ *                 (for keys produced before the factors were folded into W_K):
+ *                 the fp32 product is rounded to fp32, then to fp16, as a plain
+ *                 fp32 multiply followed by a conversion does.
  * Quantiser arithmetic is IEEE fp32 on the fp16 inputs, scale rounded to fp16
  * before the codes are formed, round-half-to-even.  On success
  * cache->n_tokens += t_new.  INNERQ_E_CAPACITY if the result would exceed
@@ -177,7 +179,8 @@ int innerq_quantize_append(const innerq_config_t *cfg, innerq_cache_t *cache, co
  * the softmax is normalised (Figure "quantization_overall").
  *   q_fp16     device, fp16 [B][Hq][d], read only
  *   q_scale    device, fp32 [Hk][d] or NULL.  When given, the query of head hq
- *              is first replaced by fp16(float(q) * q_scale[hq/(Hq/Hk)][c])
+ *              is first replaced by fp16(float(q) * q_scale[hq/(Hq/Hk)][c]), rounded
+ *              in the same two steps as the keys,
  *              (for callers that have not folded the key norm into W_Q).
  *   out        device, [B][Hq][d], fp32 if out_is_fp32 else fp16
  *   workspace  device scratch of at least innerq_workspace_bytes(cfg) bytes;

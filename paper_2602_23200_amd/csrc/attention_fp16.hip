@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float qv = 0.f;
     if (h < r) {
       const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h) * D + c];
-      qv = a.q_scale ? __half2float(__float2half_rn(__half2float(qh) * a.q_scale[hk * D + c])) : __half2float(qh);
+      qv = a.q_scale ? __half2float(scaled_half(__half2float(qh), a.q_scale[hk * D + c])) : __half2float(qh);
     }
     qs[h][c] = (_Float16)qv;
   }

@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(256) attention_generic_kernel(AttnArgs a, long
     float qv = 0.f;
     if (h < nh) {
       const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h0 + h) * D + c];
-      qv = a.q_scale ? h2f(__float2half_rn(h2f(qh) * a.q_scale[hk * D + c])) : h2f(qh);
+      qv = a.q_scale ? h2f(scaled_half(h2f(qh), a.q_scale[hk * D + c])) : h2f(qh);
     }
     q_s[h][c] = qv;
   }

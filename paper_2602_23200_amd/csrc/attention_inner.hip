@@ -258,7 +258,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (e & 1) ? (rw[e / 2] >> 16) : (rw[e / 2] & 0xffffu);
       float qv = __half2float(__ushort_as_half((unsigned short)hb));
-      if (a.q_scale) qv = __half2float(__float2half_rn(qv * a.q_scale[hk * D + c0 + e]));
+      if (a.q_scale) qv = __half2float(scaled_half(qv, a.q_scale[hk * D + c0 + e]));
       part += qv;
       const int c = c0 + e;
       const int word = c / FK::FPW, ep = c % FK::FPW;

@@ -39,6 +39,16 @@ struct TensorView {
   long long n_quant;   // tokens currently in the quantised store
 };
 
+// fp16_rn(fp32_rn(x * s)): a key (or query) times its normalisation factor, rounded the way a plain fp32
+// multiply followed by a conversion rounds it.  Left alone, the compiler merges the two into one
+// mixed-precision instruction that rounds the exact product once, and about one element in 2^13
+// (an fp32 product that lands on an fp16 midpoint) then differs by one fp16 step.
+__device__ inline __half scaled_half(float x, float s) {
+  float p = x * s;
+  asm("" : "+v"(p));
+  return __float2half_rn(p);
+}
+
 struct Partition { long long n_sink, n_quant, n_recent; };
 
 inline int bits_of(const innerq_config_t& c, int which) { return (which == 1 && c.v_bits) ? c.v_bits : c.bits; }

@@ -253,7 +253,7 @@ __device__ inline void window_copy(const QuantArgs& a, const QuantTensorJob& j, 
     __half* h = reinterpret_cast<__half*>(&raw);
     const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
+    for (int e = 0; e < 8; ++e) h[e] = scaled_half(h2f(h[e]), inv[e]);
   }
   *reinterpret_cast<uint4*>(dst + ch * 8) = raw;
 }
@@ -299,7 +299,7 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
     if (from_new && j.normalise) {
       const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G + sub * E;
 #pragma unroll
-      for (int i = 0; i < E; ++i) x[i] = h2f(__float2half_rn(x[i] * inv[i]));
+      for (int i = 0; i < E; ++i) x[i] = h2f(scaled_half(x[i], inv[i]));
     }
     __half s, z;
     uint32_t word_hi;
@@ -327,7 +327,7 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
       bool from_new;
       const __half* src = token_row(j, a, bh, a.w_sink + tg * G + i, from_new);
       float v = h2f(src[c]);
-      if (from_new && j.normalise) v = h2f(__float2half_rn(v * inv));
+      if (from_new && j.normalise) v = h2f(scaled_half(v, inv));
       return v;
     };
     uint32_t words[W];
@@ -361,7 +361,7 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
       __half* h = reinterpret_cast<__half*>(&raw);
       const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) h[e] = __float2half_rn(h2f(h[e]) * inv[e]);
+      for (int e = 0; e < 8; ++e) h[e] = scaled_half(h2f(h[e]), inv[e]);
     }
     __half* dst = reinterpret_cast<__half*>(j.codes) + (bh * a.capacity + row) * kHeadDim + ch * 8;
     *reinterpret_cast<uint4*>(dst) = raw;

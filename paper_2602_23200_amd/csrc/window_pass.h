@@ -197,7 +197,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           float qv = (e & 1) ? window_half_hi(rw[e / 2]) : window_half_lo(rw[e / 2]);
-          if (a.q_scale) qv = __half2float(__float2half_rn(qv * a.q_scale[hk * D + c0 + e]));
+          if (a.q_scale) qv = __half2float(scaled_half(qv, a.q_scale[hk * D + c0 + e]));
           wq[h][c0 + e] = (_Float16)qv;
           if constexpr (KQ) wqf[c0 + e][h] = qv;
           part += qv;

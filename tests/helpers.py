@@ -103,3 +103,28 @@ def max_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     num = np.abs(got.astype(np.float64) - want).max(axis=-1)
     den = np.abs(want).max(axis=-1)
     return float((num / den).max())
+
+
+def midpoint_scale_and_values(d: int, n: int, seed: int, lo_exp: int, hi_exp: int):
+    """An fp32 factor per channel, scale [d] in [0.25, 1), and fp16 values [n, d] with magnitudes in
+    [2^lo_exp, 2^hi_exp), such that EVERY product value x scale changes when it is rounded to fp32
+    before it is rounded to fp16: the exact product lies just beside an fp16 midpoint and its fp32
+    rounding lands on it.  Only the 10 mantissa bits of a value matter, and a given factor has
+    such a mantissa with probability of about 1/16, so factors are drawn until one has."""
+    rng = np.random.default_rng(seed)
+    mant = (np.arange(1024, 2048, dtype=np.float32) / np.float32(1024)).astype(np.float16)   # [1, 2)
+    scale = np.empty(d, dtype=np.float32)
+    out = np.empty((n, d), dtype=np.float16)
+    for c in range(d):
+        while True:
+            s = np.float32(rng.uniform(0.25, 1.0))
+            twice = (mant.astype(np.float32) * s).astype(np.float16)
+            once = (mant.astype(np.float64) * np.float64(s)).astype(np.float16)    # exact product, one rounding
+            pick = mant[twice != once]
+            if pick.size:
+                break
+        scale[c] = s
+        v = pick[rng.integers(0, pick.size, n)].astype(np.float32)
+        v *= np.exp2(rng.integers(lo_exp, hi_exp, n)).astype(np.float32) * rng.choice(np.float32([-1, 1]), n)
+        out[:, c] = v.astype(np.float16)
+    return scale, out

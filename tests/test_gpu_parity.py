@@ -9,7 +9,7 @@ import pytest
 
 from oracle import innerq_oracle as orc
 from paper_2602_23200_amd import workloads as wl
-from tests.helpers import (assert_cache_equal, gpu_buffer_as_numpy, gpu_config, max_rel_err,
+from tests.helpers import (assert_cache_equal, midpoint_scale_and_values, gpu_buffer_as_numpy, gpu_config, max_rel_err,
                            oracle_config)
 
 pytestmark = pytest.mark.gpu
@@ -224,6 +224,30 @@ def test_key_norm_unfolded_path_matches_oracle_and_folded(env):
     assert np.array_equal(got, got2)
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_key_norm_keeps_the_fp32_rounding_of_the_product(env, kind):
+    """Keys and queries chosen so that rounding the exact product K x inv_norm (q x norm) once gives
+    a different fp16 value than rounding it to fp32 first: windows, codes and scales must still be
+    the oracle's, bit for bit."""
+    torch, iq = env
+    w = small(n_tokens=4 + 16 * 32 + 32, batch=1, n_kv_heads=2, n_q_heads=4)
+    o = oracle_config(w, kind=kind)
+    ks = [midpoint_scale_and_values(w.head_dim, w.n_tokens, seed=h, lo_exp=-1, hi_exp=3) for h in range(w.n_kv_heads)]
+    inv = np.stack([k[0] for k in ks])
+    K = np.stack([k[1] for k in ks])[None]
+    V = wl.kv_full(w)[1]
+    r = w.n_q_heads // w.n_kv_heads
+    # the query factor need not be the reciprocal of the key factor for this check
+    qs = [midpoint_scale_and_values(w.head_dim, r, seed=50 + h, lo_exp=-6, hi_exp=-3) for h in range(w.n_kv_heads)]
+    norm = np.stack([x[0] for x in qs])
+    q = np.concatenate([x[1] for x in qs])[None]
+    want_cache = orc.cache_init_prefill(o, K, V, k_inv_norm=inv)
+    want = orc.decode_attention(o, want_cache, q, q_scale=norm)
+    g, got = run_attention(torch, iq, o, K, V, q, k_inv_norm=inv, q_scale=norm)
+    assert_cache_equal(g, want_cache, o)
+    assert max_rel_err(got, want) <= TOL
+
+
 @pytest.mark.parametrize("name", ["tiny", "llama2_7b_4k"])
 def test_attention_baseline_configs_full(env, name):
     torch, iq = env
@@ -271,6 +295,54 @@ def test_attention_baseline_configs_full_size_sampled(env, name, slabs):
         want_cache = orc.cache_init_prefill(o1, k[None, None], v[None, None])
         assert_cache_equal(g, want_cache, o1, bsel=slice(b, b + 1), hsel=slice(h, h + 1), what=f"slab {b},{h}")
         want = orc.decode_attention(o1, want_cache, q[b:b + 1, h * r:(h + 1) * r])
+        assert max_rel_err(got[b:b + 1, h * r:(h + 1) * r], want) <= TOL
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_long_context_layer_full_size_sampled_with_folded_key_norm(env, layer):
+    """One layer of the 128k-token configuration at full size, key normalisation folded the way the
+    benchmark does it (factors calibrated over the prefill keys, keys divided on their way into the
+    cache, the query multiplied).  The oracle recomputes two (batch, kv-head) slabs on their own."""
+    torch, iq = env
+    w = wl.WORKLOADS["llama3_8b_128k_32L"]
+    o = oracle_config(w)
+    B, Hk, N, d = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim
+    slabs = [(0, 0), (3, 7)]
+    # the sampled slabs come from the host generator; the others are drawn on the device with the
+    # same per-channel scales (the host generator needs minutes for a whole layer of this size)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 + layer)
+    sigma = to_dev(torch, wl.key_channel_sigma(w, layer).astype(np.float32))       # [Hk, d]
+    Kd = (torch.randn((B, Hk, N, d), device="cuda", generator=gen) * sigma[None, :, None, :]).half()
+    Vd = torch.randn((B, Hk, N, d), device="cuda", generator=gen).half()
+    keep = {}
+    for (b, h) in slabs:
+        k, v = wl.kv_slab(w, b, h, layer)
+        Kd[b, h].copy_(torch.from_numpy(k))
+        Vd[b, h].copy_(torch.from_numpy(v))
+        keep[(b, h)] = (k, v)
+    peak = Kd.abs().amax(dim=(0, 2)).cpu().numpy()[None, :, None, :]      # max |K| per head and channel
+    norm, inv = orc.calibrate_key_norm(peak, per_head=False)
+    cfg = gpu_config(o)
+    got_norm, got_inv = iq.innerq_calibrate_key_norm(cfg, Kd, per_head=False)
+    assert np.array_equal(got_norm.cpu().numpy(), norm)
+    assert np.array_equal(got_inv.cpu().numpy(), inv)
+    q = wl.query(w, layer)
+    g = iq.allocate_cache(cfg)
+    iq.innerq_quantize_append(g, Kd, Vd, k_inv_norm=to_dev(torch, inv))
+    del Kd, Vd
+    ws = iq.allocate_workspace(g.cfg)
+    got = iq.innerq_decode_attention(g, to_dev(torch, q), ws, q_scale=to_dev(torch, norm))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert np.isfinite(got).all()
+    r = w.n_q_heads // w.n_kv_heads
+    o1 = oracle_config(w.with_(batch=1, n_kv_heads=1, n_q_heads=r))
+    for (b, h), (k, v) in keep.items():
+        want_cache = orc.cache_init_prefill(o1, k[None, None], v[None, None], k_inv_norm=inv[h:h + 1])
+        assert_cache_equal(g, want_cache, o1, bsel=slice(b, b + 1), hsel=slice(h, h + 1),
+                           what=f"layer {layer} slab {b},{h}")
+        want = orc.decode_attention(o1, want_cache, q[b:b + 1, h * r:(h + 1) * r], q_scale=norm[h:h + 1])
         assert max_rel_err(got[b:b + 1, h * r:(h + 1) * r], want) <= TOL
 
 

@@ -300,3 +300,19 @@ def test_crafted_density_groups_decide_as_planned(bits):
     assert np.array_equal(np.signbit(s), planned.numpy())
     assert 0.2 < planned.float().mean().item() < 0.4
     assert np.array_equal(orc.dequantize_groups(u, s, z, bits), g.astype(np.float64))
+
+
+def test_channel_scale_rounds_the_fp32_product():
+    """K x inv_norm (and q x norm) is an fp32 multiply followed by a conversion to fp16: the same
+    two roundings torch's CPU kernels make for (x.float() * s).half().  Values whose exact
+    product sits beside an fp16 midpoint tell this apart from a single rounding of the exact
+    product; the oracle must side with the two-step result on every one of them."""
+    import torch
+
+    from tests.helpers import midpoint_scale_and_values
+    scale, x = midpoint_scale_and_values(128, 64, seed=5, lo_exp=-3, hi_exp=4)
+    got = orc.apply_channel_scale(x[None, None], scale[None])[0, 0]
+    two_step = (torch.from_numpy(x).float() * torch.from_numpy(scale)[None, :]).half().numpy()
+    one_step = (x.astype(np.float64) * scale.astype(np.float64)[None, :]).astype(np.float16)
+    assert np.array_equal(got.view(np.uint16), two_step.view(np.uint16))
+    assert (got != one_step).all()
