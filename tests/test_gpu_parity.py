@@ -414,6 +414,28 @@ def test_separate_key_and_value_widths(env, kind, k_bits, v_bits, group, k_mode,
     assert max_rel_err(out.cpu().numpy(), ref) <= TOL
 
 
+@pytest.mark.parametrize("bits,v_bits,group,k_mode,v_mode", [
+    (3, 0, 32, orc.HYBRID, orc.HYBRID), (4, 0, 32, orc.HYBRID, orc.HYBRID), (3, 2, 32, orc.SYM, orc.HYBRID),
+    (3, 0, 64, orc.HYBRID, orc.HYBRID), (4, 0, 64, orc.ASYM, orc.SYM), (2, 0, 32, orc.SYM, orc.ASYM)])
+def test_long_context_other_widths_with_key_norm(env, bits, v_bits, group, k_mode, v_mode):
+    """32k tokens of the heavy-tailed workload at the widths, group sizes and modes the full-size
+    layer tests do not reach, keys normalised on their way in: a quarter of a million groups per
+    tensor must come out bit-exact (events of one in 10^4 show at this size, not at a few hundred
+    tokens), and the long fused pass must stay within tolerance."""
+    torch, iq = env
+    w = wl.WORKLOADS["llama3_8b_32k"].with_(batch=1, n_kv_heads=2, n_q_heads=8, bits=bits, group=group,
+                                             k_mode=k_mode, v_mode=v_mode, w_recent=128 if group == 64 else 32)
+    o = oracle_config(w, v_bits=v_bits)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    norm, inv = orc.calibrate_key_norm(K, per_head=True)
+    want_cache = orc.cache_init_prefill(o, K, V, k_inv_norm=inv)
+    want = orc.decode_attention(o, want_cache, q, q_scale=norm)
+    g, got = run_attention(torch, iq, o, K, V, q, k_inv_norm=inv, q_scale=norm)
+    assert_cache_equal(g, want_cache, o, what=f"k{bits} v{v_bits} G{group}")
+    assert max_rel_err(got, want) <= TOL
+
+
 def _random_case(i):
     r = np.random.default_rng(1000 + i)
     k_bits = int(r.choice([2, 3, 4]))
