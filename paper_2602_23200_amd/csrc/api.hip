@@ -278,7 +278,10 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
       const long long nw = ceil_div(win_tokens, len);
       long long plain = per_head - nw;
       if (plain > n_tiles) plain = n_tiles;
-      if (plain > split_cap(c)) plain = split_cap(c);
+      // the workspace holds split_cap + window_chunk_cap partials; the inner kernel's wavefronts
+      // that carry a window chunk count as splits too
+      const long long most = fused_kind == 1 ? split_cap(c) - nw : split_cap(c);
+      if (plain > most) plain = most;
       if (plain < 1) plain = 1;
       const long long tile_cost = ceil_div(n_tiles, plain) * 8, win_cost = nw ? 32 + 14 * len / 8 : 0;   // x 8
       const long long cost = tile_cost > win_cost ? tile_cost : win_cost;
@@ -302,6 +305,7 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   if (n_win > window_chunk_cap(c)) return INNERQ_E_ARG;
   a.n_partials = n_splits + n_win;
   const size_t heads = (size_t)c.batch * c.n_q_heads;
+  if (heads * (size_t)a.n_partials * (kHeadDim + 2) * sizeof(float) + 64 > workspace_bytes) return INNERQ_E_WORKSPACE;
   a.ws_ml = static_cast<float*>(workspace);
   a.ws_o = a.ws_ml + ((heads * a.n_partials * 2 + 3) / 4) * 4;
 

@@ -436,6 +436,29 @@ def test_long_context_other_widths_with_key_norm(env, bits, v_bits, group, k_mod
     assert max_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_single_kv_head_long_context_uses_every_partial_slot(env, kind):
+    """One (batch, kv-head) pair and 40k tokens: the launch wants more wavefronts than the split
+    cap allows, so the number of partial results is set by the caps that size the workspace (the
+    fused inner kernel's window-carrying wavefronts count against the split cap).  A guard band
+    behind the workspace must stay untouched and the result must match the oracle."""
+    torch, iq = env
+    w = wl.WORKLOADS["llama3_8b_32k"].with_(batch=1, n_kv_heads=1, n_q_heads=4, n_tokens=40000)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K), to_dev(torch, V))
+    need = iq.innerq_workspace_bytes(g.cfg)
+    guard = 1 << 16
+    buf = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+    out = iq.innerq_decode_attention(g, to_dev(torch, q), buf[:need])
+    torch.cuda.synchronize()
+    assert bool((buf[need:] == 0x5A).all())
+    assert max_rel_err(out.cpu().numpy(), want) <= TOL
+
+
 def _random_case(i):
     r = np.random.default_rng(1000 + i)
     k_bits = int(r.choice([2, 3, 4]))
