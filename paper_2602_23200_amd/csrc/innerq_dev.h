@@ -77,6 +77,7 @@ struct QuantTensorJob {
   uint8_t* codes; __half* scales; __half* zeros; __half* sink; __half* ring;
   const __half* x_new;       // [B][Hk][t_new][d]
   int form, mode, slots, bits;
+  int lanes;                      // per-token form: lanes that share one group (8: short calls, 1: bulk)
   long long row_begin, row_end;   // store rows to quantise in this call (token = w_sink + row)
   long long ring_from;            // new tokens with index >= ring_from go to the ring
   int normalise;                  // apply k_inv_norm to tokens taken from x_new

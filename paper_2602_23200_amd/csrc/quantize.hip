@@ -18,6 +18,67 @@ __device__ inline float h2f(__half h) { return __half2float(h); }
 //                                 only if its error is strictly smaller
 // The scale is rounded to fp16 (its stored precision) before the codes are formed.
 // Stored field: code (asymmetric) or code + 2^(b-1) (symmetric); scale sign bit = asymmetric.
+// The correctly rounded fp32 quotient num / S, given r = fl(1 / S) correctly rounded (one IEEE
+// division per group instead of one per element): q0 = fl(num * r) is within one ulp, the
+// remainder num - S * q0 is exact in the fused multiply-add, and q0 + rem * r then rounds to
+// the nearest fp32 to num / S (Markstein's division step; no underflow at these magnitudes:
+// num is a multiple of 2^-24 below 2^17, S an fp16 value).  S == 0 gives NaN or infinity like the
+// plain division; the callers force the code to 0 in that case.
+__device__ inline float code_quotient(float num, float S, float r) {
+  const float q0 = num * r;
+  const float rem = __builtin_fmaf(-S, q0, num);
+  return __builtin_fmaf(rem, r, q0);
+}
+
+// One pass over a group held in registers: packed fields and L1 error of the asymmetric and of
+// the symmetric variant (each only if the mode can choose it).
+template <int G, int BITS>
+__device__ inline void group_codes(const float (&x)[G], int mode, float mn, float Saf, float Ssf,
+                                   uint32_t (&wa)[G * BITS / 32], uint32_t (&ws)[G * BITS / 32], float& ea,
+                                   float& es) {
+  constexpr int W = G * BITS / 32;
+  constexpr int QMAX = (1 << BITS) - 1;
+  constexpr int HALF = 1 << (BITS - 1);
+#pragma unroll
+  for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
+  ea = 0.f; es = 0.f;
+  if (mode != INNERQ_SYM) {
+    const float rS = 1.0f / Saf;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      float ca = fminf(fmaxf(rintf(code_quotient(x[i] - mn, Saf, rS)), 0.f), (float)QMAX);
+      ca = (Saf == 0.f) ? 0.f : ca;
+      const float ra = Saf * ca + mn;
+      ea = ea + fabsf(x[i] - ra);
+      const uint32_t ua = (uint32_t)(int)ca;
+      if constexpr (BITS == 3) {
+        // a plane of 2-bit low parts (G/16 words), then a plane of high bits
+        wa[(i * 2) / 32] |= (ua & 3u) << ((i * 2) % 32);
+        wa[G / 16 + i / 32] |= (ua >> 2) << (i % 32);
+      } else {
+        wa[(i * BITS) / 32] |= ua << ((i * BITS) % 32);
+      }
+    }
+  }
+  if (mode != INNERQ_ASYM) {
+    const float rS = 1.0f / Ssf;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      float cs = fminf(fmaxf(rintf(code_quotient(x[i], Ssf, rS)), (float)(-HALF)), (float)(HALF - 1));
+      cs = (Ssf == 0.f) ? 0.f : cs;
+      const float rs = Ssf * cs;
+      es = es + fabsf(x[i] - rs);
+      const uint32_t us = (uint32_t)((int)cs + HALF);
+      if constexpr (BITS == 3) {
+        ws[(i * 2) / 32] |= (us & 3u) << ((i * 2) % 32);
+        ws[G / 16 + i / 32] |= (us >> 2) << (i % 32);
+      } else {
+        ws[(i * BITS) / 32] |= us << ((i * BITS) % 32);
+      }
+    }
+  }
+}
+
 template <int G, int BITS>
 __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den_literal,
                                       uint32_t (&words)[G * BITS / 32], __half& scale, __half& zero) {
@@ -36,31 +97,8 @@ __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
   uint32_t wa[W], ws[W];
-#pragma unroll
-  for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
-  float ea = 0.f, es = 0.f;
-#pragma unroll
-  for (int i = 0; i < G; ++i) {
-    float ca = fminf(fmaxf(rintf((x[i] - mn) / Saf), 0.f), (float)QMAX);
-    ca = (Saf == 0.f) ? 0.f : ca;
-    float cs = fminf(fmaxf(rintf(x[i] / Ssf), (float)(-HALF)), (float)(HALF - 1));
-    cs = (Ssf == 0.f) ? 0.f : cs;
-    const float ra = Saf * ca + mn;
-    const float rs = Ssf * cs;
-    ea = ea + fabsf(x[i] - ra);
-    es = es + fabsf(x[i] - rs);
-    const uint32_t ua = (uint32_t)(int)ca, us = (uint32_t)((int)cs + HALF);
-    if constexpr (BITS == 3) {
-      // a plane of 2-bit low parts (G/16 words), then a plane of high bits
-      wa[(i * 2) / 32] |= (ua & 3u) << ((i * 2) % 32);
-      ws[(i * 2) / 32] |= (us & 3u) << ((i * 2) % 32);
-      wa[G / 16 + i / 32] |= (ua >> 2) << (i % 32);
-      ws[G / 16 + i / 32] |= (us >> 2) << (i % 32);
-    } else {
-      wa[(i * BITS) / 32] |= ua << ((i * BITS) % 32);
-      ws[(i * BITS) / 32] |= us << ((i * BITS) % 32);
-    }
-  }
+  float ea, es;
+  group_codes<G, BITS>(x, mode, mn, Saf, Ssf, wa, ws, ea, es);
   const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
 #pragma unroll
   for (int i = 0; i < W; ++i) words[i] = asym ? wa[i] : ws[i];
@@ -91,6 +129,7 @@ __device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_li
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
+  const float rSa = 1.0f / Saf, rSs = 1.0f / Ssf;
   uint32_t wa[W], ws[W];
 #pragma unroll
   for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
@@ -102,9 +141,9 @@ __device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_li
     for (int f = 0; f < FPW; ++f) {
       const int i = w * FPW + f;
       const float v = x(i);
-      float ca = fminf(fmaxf(rintf((v - mn) / Saf), 0.f), (float)QMAX);
+      float ca = fminf(fmaxf(rintf(code_quotient(v - mn, Saf, rSa)), 0.f), (float)QMAX);
       ca = (Saf == 0.f) ? 0.f : ca;
-      float cs = fminf(fmaxf(rintf(v / Ssf), (float)(-HALF)), (float)(HALF - 1));
+      float cs = fminf(fmaxf(rintf(code_quotient(v, Ssf, rSs)), (float)(-HALF)), (float)(HALF - 1));
       cs = (Ssf == 0.f) ? 0.f : cs;
       const float ra = Saf * ca + mn;
       const float rs = Ssf * cs;
@@ -172,13 +211,14 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
+  const float rSa = 1.0f / Saf, rSs = 1.0f / Ssf;
   uint32_t fa = 0u, fs = 0u, ha = 0u, hs = 0u;
   float da[E], ds[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    float ca = fminf(fmaxf(rintf((x[i] - mn) / Saf), 0.f), (float)QMAX);
+    float ca = fminf(fmaxf(rintf(code_quotient(x[i] - mn, Saf, rSa)), 0.f), (float)QMAX);
     ca = (Saf == 0.f) ? 0.f : ca;
-    float cs = fminf(fmaxf(rintf(x[i] / Ssf), (float)(-HALF)), (float)(HALF - 1));
+    float cs = fminf(fmaxf(rintf(code_quotient(x[i], Ssf, rSs)), (float)(-HALF)), (float)(HALF - 1));
     cs = (Ssf == 0.f) ? 0.f : cs;
     const float ra = Saf * ca + mn;
     const float rs = Ssf * cs;
@@ -234,20 +274,34 @@ __device__ inline const __half* token_row(const QuantTensorJob& j, const QuantAr
   return j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
 }
 
+// Which of the t_new new tokens (index i, absolute token n_old + i) go to a window: i < n_a to
+// the sink, i >= i_b to the recent ring; the ones between were quantised by this same call.
+struct CopySpan { long long n_a, i_b; };
+__host__ __device__ inline CopySpan copy_span(const QuantArgs& a, const QuantTensorJob& j) {
+  long long n_a = a.w_sink - a.n_old;
+  n_a = n_a < 0 ? 0 : (n_a > a.t_new ? a.t_new : n_a);
+  long long i_b = j.ring_from - a.n_old;
+  i_b = i_b < n_a ? n_a : (i_b > a.t_new ? a.t_new : i_b);
+  return {n_a, i_b};
+}
+
 // New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
 // ring -- unless this same call already moved them on to the quantised store.
 __device__ inline void window_copy(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
   constexpr int CPR = kHeadDim / 8;
   const long long BH = (long long)a.batch * a.n_kv_heads;
-  if (idx >= BH * a.t_new * CPR) return;
+  // only the new tokens that stay in a window are visited: the first n_a (sink) and those from i_b on (ring)
+  const CopySpan sp = copy_span(a, j);
+  const long long n_cp = sp.n_a + (a.t_new - sp.i_b);
+  if (idx >= BH * n_cp * CPR) return;
   const int ch = (int)(idx % CPR);
-  const long long i = (idx / CPR) % a.t_new;
-  const long long bh = idx / (CPR * a.t_new);
+  const long long k = (idx / CPR) % n_cp;
+  const long long bh = idx / (CPR * n_cp);
+  const long long i = k < sp.n_a ? k : sp.i_b + (k - sp.n_a);
   const long long t = a.n_old + i;
   __half* dst;
   if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
-  else if (t >= j.ring_from) dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
-  else return;
+  else dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
   uint4 raw = *reinterpret_cast<const uint4*>(j.x_new + (bh * a.t_new + i) * kHeadDim + ch * 8);
   if (j.normalise) {
     __half* h = reinterpret_cast<__half*>(&raw);
@@ -270,7 +324,56 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
   const long long BH = (long long)a.batch * a.n_kv_heads;
   constexpr int W = G * BITS / 32;
 
-  if (j.form == kPerToken) {
+  if (j.form == kPerToken && j.lanes == 1) {
+    // bulk calls: one lane per group (its G channels are 2 G contiguous bytes).  No cross-lane
+    // traffic, and a wavefront has 64 groups' worth of loads in flight.
+    constexpr int GPR = kHeadDim / G;                    // groups per row
+    if (idx >= BH * n_rows * GPR) return;
+    const int g = (int)(idx % GPR);
+    const long long row = j.row_begin + (idx / GPR) % n_rows;
+    const long long bh = idx / (GPR * n_rows);
+    bool from_new;
+    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G;
+    const bool norm = from_new && j.normalise;
+    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G;
+    uint32_t words[W];
+    __half s, z;
+    if constexpr (G <= 32) {
+      float x[G];
+#pragma unroll
+      for (int p = 0; p < G / 8; ++p) {
+        const uint4 raw = reinterpret_cast<const uint4*>(src)[p];
+        const __half* h = reinterpret_cast<const __half*>(&raw);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[8 * p + e] = h2f(h[e]);
+      }
+      if (norm) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) x[i] = h2f(scaled_half(x[i], inv[i]));
+      }
+      quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+    } else {
+      auto fetch = [&](int i) -> float {
+        float v = h2f(src[i]);
+        if (norm) v = h2f(scaled_half(v, inv[i]));
+        return v;
+      };
+      quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+    }
+    // a row is one plane of LB-bit fields over all channels (3-bit: followed by the plane of high bits)
+    constexpr int LB = BITS == 3 ? 2 : BITS;
+    constexpr int WL = G * LB / 32;                      // words of the (low) plane of one group
+    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8);
+#pragma unroll
+    for (int i = 0; i < WL; ++i) rowp[g * WL + i] = words[i];
+    if constexpr (BITS == 3) {
+#pragma unroll
+      for (int i = 0; i < G / 32; ++i) rowp[kHeadDim * 2 / 32 + g * (G / 32) + i] = words[WL + i];
+    }
+    const long long so = (bh * a.capacity + row) * GPR + g;
+    j.scales[so] = s;
+    if (j.zeros) j.zeros[so] = z;
+  } else if (j.form == kPerToken) {
     // 8 lanes per group, G/8 consecutive channels each
     constexpr int GPR = kHeadDim / G;                    // groups per row
     constexpr int E = G / 8;
@@ -393,12 +496,17 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
     const long long rows = j.row_end - j.row_begin;
     if (rows <= 0) continue;
     long long n = 0;
-    if (j.form == kPerToken) n = BH * rows * (kHeadDim / G) * 8;
+    if (j.form == kPerToken) n = BH * rows * (kHeadDim / G) * j.lanes;
     else if (j.form == kPerChannel) n = BH * (rows / G) * kHeadDim;
     else n = BH * rows * (kHeadDim / 8);
     threads = n > threads ? n : threads;
   }
-  const long long cthreads = BH * a.t_new * (kHeadDim / 8);
+  long long cthreads = 0;
+  for (int w = 0; w < 2; ++w) {
+    const CopySpan sp = copy_span(a, a.job[w]);
+    const long long n = BH * (sp.n_a + (a.t_new - sp.i_b)) * (kHeadDim / 8);
+    cthreads = n > cthreads ? n : cthreads;
+  }
   // A new token may overwrite a ring slot only after the old token in it has been read.  If
   // every token from the oldest one evicted in this call to the newest one appended fits the
   // ring at once, no slot is shared and one launch does both jobs.
@@ -421,6 +529,7 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (cthreads == 0) return hipSuccess;
   dim3 grid((unsigned)((cthreads + 255) / 256), 2);
   window_copy_kernel<<<grid, 256, 0, stream>>>(a);
   return hipGetLastError();
