@@ -22,13 +22,16 @@ __device__ inline float h2f(__half h) { return __half2float(h); }
 // division per group instead of one per element): q0 = fl(num * r) is within one ulp, the
 // remainder num - S * q0 is exact in the fused multiply-add, and q0 + rem * r then rounds to
 // the nearest fp32 to num / S (Markstein's division step; no underflow at these magnitudes:
-// num is a multiple of 2^-24 below 2^17, S an fp16 value).  S == 0 gives NaN or infinity like the
-// plain division; the callers force the code to 0 in that case.
+// num is a multiple of 2^-24 below 2^17, S an fp16 value).  Callers pass r = 0 for S == 0.
 __device__ inline float code_quotient(float num, float S, float r) {
   const float q0 = num * r;
   const float rem = __builtin_fmaf(-S, q0, num);
   return __builtin_fmaf(rem, r, q0);
 }
+
+// 1 / S for code_quotient, 0 for S == 0: every quotient of such a group is then exactly 0, which
+// is the code the formula assigns when the scale is 0.
+__device__ inline float group_reciprocal(float S) { return S == 0.f ? 0.f : 1.0f / S; }
 
 // One pass over a group held in registers: packed fields and L1 error of the asymmetric and of
 // the symmetric variant (each only if the mode can choose it).
@@ -43,11 +46,10 @@ __device__ inline void group_codes(const float (&x)[G], int mode, float mn, floa
   for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
   ea = 0.f; es = 0.f;
   if (mode != INNERQ_SYM) {
-    const float rS = 1.0f / Saf;
+    const float rS = group_reciprocal(Saf);
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      float ca = fminf(fmaxf(rintf(code_quotient(x[i] - mn, Saf, rS)), 0.f), (float)QMAX);
-      ca = (Saf == 0.f) ? 0.f : ca;
+      const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i] - mn, Saf, rS)), 0.f, (float)QMAX);
       const float ra = Saf * ca + mn;
       ea = ea + fabsf(x[i] - ra);
       const uint32_t ua = (uint32_t)(int)ca;
@@ -61,11 +63,10 @@ __device__ inline void group_codes(const float (&x)[G], int mode, float mn, floa
     }
   }
   if (mode != INNERQ_ASYM) {
-    const float rS = 1.0f / Ssf;
+    const float rS = group_reciprocal(Ssf);
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      float cs = fminf(fmaxf(rintf(code_quotient(x[i], Ssf, rS)), (float)(-HALF)), (float)(HALF - 1));
-      cs = (Ssf == 0.f) ? 0.f : cs;
+      const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i], Ssf, rS)), (float)(-HALF), (float)(HALF - 1));
       const float rs = Ssf * cs;
       es = es + fabsf(x[i] - rs);
       const uint32_t us = (uint32_t)((int)cs + HALF);
@@ -129,7 +130,7 @@ __device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_li
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
-  const float rSa = 1.0f / Saf, rSs = 1.0f / Ssf;
+  const float rSa = group_reciprocal(Saf), rSs = group_reciprocal(Ssf);
   uint32_t wa[W], ws[W];
 #pragma unroll
   for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
@@ -141,10 +142,8 @@ __device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_li
     for (int f = 0; f < FPW; ++f) {
       const int i = w * FPW + f;
       const float v = x(i);
-      float ca = fminf(fmaxf(rintf(code_quotient(v - mn, Saf, rSa)), 0.f), (float)QMAX);
-      ca = (Saf == 0.f) ? 0.f : ca;
-      float cs = fminf(fmaxf(rintf(code_quotient(v, Ssf, rSs)), (float)(-HALF)), (float)(HALF - 1));
-      cs = (Ssf == 0.f) ? 0.f : cs;
+      const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(v - mn, Saf, rSa)), 0.f, (float)QMAX);
+      const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(v, Ssf, rSs)), (float)(-HALF), (float)(HALF - 1));
       const float ra = Saf * ca + mn;
       const float rs = Ssf * cs;
       ea = ea + fabsf(v - ra);
@@ -211,15 +210,13 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
   const __half Ss = __float2half_rn(am / den);
   const float Saf = h2f(Sa), Ssf = h2f(Ss);
-  const float rSa = 1.0f / Saf, rSs = 1.0f / Ssf;
+  const float rSa = group_reciprocal(Saf), rSs = group_reciprocal(Ssf);
   uint32_t fa = 0u, fs = 0u, ha = 0u, hs = 0u;
   float da[E], ds[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    float ca = fminf(fmaxf(rintf(code_quotient(x[i] - mn, Saf, rSa)), 0.f), (float)QMAX);
-    ca = (Saf == 0.f) ? 0.f : ca;
-    float cs = fminf(fmaxf(rintf(code_quotient(x[i], Ssf, rSs)), (float)(-HALF)), (float)(HALF - 1));
-    cs = (Ssf == 0.f) ? 0.f : cs;
+    const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i] - mn, Saf, rSa)), 0.f, (float)QMAX);
+    const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i], Ssf, rSs)), (float)(-HALF), (float)(HALF - 1));
     const float ra = Saf * ca + mn;
     const float rs = Ssf * cs;
     da[i] = fabsf(x[i] - ra);
@@ -426,23 +423,36 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
     const long long tg = j.row_begin / G + (idx / kHeadDim) % n_groups;   // token-group index in the store
     const long long bh = idx / (kHeadDim * n_groups);
     const float inv = j.normalise ? a.inv_norm[(bh % a.n_kv_heads) * kHeadDim + c] : 1.f;
-    auto fetch = [&](int i) -> float {
-      bool from_new;
-      const __half* src = token_row(j, a, bh, a.w_sink + tg * G + i, from_new);
-      float v = h2f(src[c]);
-      if (from_new && j.normalise) v = h2f(scaled_half(v, inv));
-      return v;
-    };
     uint32_t words[W];
     __half s, z;
-    if constexpr (G <= 32) {
-      float x[G];
+    auto run = [&](auto fetch) {
+      if constexpr (G <= 32) {
+        float x[G];
 #pragma unroll
-      for (int i = 0; i < G; ++i) x[i] = fetch(i);
-      quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+        for (int i = 0; i < G; ++i) x[i] = fetch(i);
+        quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+      } else {
+        // 64 values do not fit the register file next to the rest: fetch each element twice
+        quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+      }
+    };
+    const long long t0 = a.w_sink + tg * G;              // first token of the group
+    if (t0 >= a.n_old) {
+      // the whole group comes from x_new (bulk calls): one base address, a fixed stride
+      const __half* src0 = j.x_new + ((bh * a.t_new) + (t0 - a.n_old)) * kHeadDim + c;
+      run([&](int i) -> float {
+        float v = h2f(src0[i * kHeadDim]);
+        if (j.normalise) v = h2f(scaled_half(v, inv));
+        return v;
+      });
     } else {
-      // 64 values do not fit the register file next to the rest: fetch each element twice
-      quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+      run([&](int i) -> float {
+        bool from_new;
+        const __half* src = token_row(j, a, bh, t0 + i, from_new);
+        float v = h2f(src[c]);
+        if (from_new && j.normalise) v = h2f(scaled_half(v, inv));
+        return v;
+      });
     }
     const long long go = (bh * (a.capacity / G) + tg) * kHeadDim + c;
     uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes) + go * W;
