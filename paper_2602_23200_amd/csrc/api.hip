@@ -216,7 +216,7 @@ int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, co
     // per-token form: eight lanes share a group when the call is short (a decode step: the
     // dependent chain is what costs), one lane takes a whole group when there is bulk to fill the chip
     const long long groups = (long long)cfg->batch * cfg->n_kv_heads * (j.row_end - j.row_begin) * (kHeadDim / cfg->group);
-    j.lanes = (groups >= 4096 && cfg->group <= 32) ? 1 : 8;   // 64-channel groups do not fit one lane's registers
+    j.lanes = groups >= 4096 ? 1 : 8;
     j.normalise = (w == 0 && k_inv_norm) ? 1 : 0;
   }
   const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream));

@@ -35,8 +35,8 @@ __device__ inline float group_reciprocal(float S) { return S == 0.f ? 0.f : 1.0f
 
 // One pass over a group held in registers: packed fields and L1 error of the asymmetric and of
 // the symmetric variant (each only if the mode can choose it).
-template <int G, int BITS>
-__device__ inline void group_codes(const float (&x)[G], int mode, float mn, float Saf, float Ssf,
+template <int G, int BITS, typename X>
+__device__ inline void group_codes(X x, int mode, float mn, float Saf, float Ssf,
                                    uint32_t (&wa)[G * BITS / 32], uint32_t (&ws)[G * BITS / 32], float& ea,
                                    float& es) {
   constexpr int W = G * BITS / 32;
@@ -49,9 +49,9 @@ __device__ inline void group_codes(const float (&x)[G], int mode, float mn, floa
     const float rS = group_reciprocal(Saf);
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i] - mn, Saf, rS)), 0.f, (float)QMAX);
+      const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(x(i) - mn, Saf, rS)), 0.f, (float)QMAX);
       const float ra = Saf * ca + mn;
-      ea = ea + fabsf(x[i] - ra);
+      ea = ea + fabsf(x(i) - ra);
       const uint32_t ua = (uint32_t)(int)ca;
       if constexpr (BITS == 3) {
         // a plane of 2-bit low parts (G/16 words), then a plane of high bits
@@ -66,9 +66,9 @@ __device__ inline void group_codes(const float (&x)[G], int mode, float mn, floa
     const float rS = group_reciprocal(Ssf);
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(x[i], Ssf, rS)), (float)(-HALF), (float)(HALF - 1));
+      const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(x(i), Ssf, rS)), (float)(-HALF), (float)(HALF - 1));
       const float rs = Ssf * cs;
-      es = es + fabsf(x[i] - rs);
+      es = es + fabsf(x(i) - rs);
       const uint32_t us = (uint32_t)((int)cs + HALF);
       if constexpr (BITS == 3) {
         ws[(i * 2) / 32] |= (us & 3u) << ((i * 2) % 32);
@@ -80,18 +80,21 @@ __device__ inline void group_codes(const float (&x)[G], int mode, float mn, floa
   }
 }
 
-template <int G, int BITS>
-__device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den_literal,
+// x(i), i = 0 .. G-1 with i a compile-time constant after unrolling, returns element i of the group
+// (a register array of floats, or packed fp16 pairs for groups too large to hold as floats).
+template <int G, int BITS, typename X>
+__device__ inline void quantize_group(X x, int mode, int sym_den_literal,
                                       uint32_t (&words)[G * BITS / 32], __half& scale, __half& zero) {
   constexpr int W = G * BITS / 32;
   constexpr int QMAX = (1 << BITS) - 1;
   constexpr int HALF = 1 << (BITS - 1);
-  float mn = x[0], mx = x[0], am = fabsf(x[0]);
+  float mn = x(0), mx = mn, am = fabsf(mn);
 #pragma unroll
   for (int i = 1; i < G; ++i) {
-    mn = fminf(mn, x[i]);
-    mx = fmaxf(mx, x[i]);
-    am = fmaxf(am, fabsf(x[i]));
+    const float v = x(i);
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+    am = fmaxf(am, fabsf(v));
   }
   const float den = sym_den_literal ? (float)QMAX : (float)(HALF - 1);
   const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
@@ -107,70 +110,11 @@ __device__ inline void quantize_group(const float (&x)[G], int mode, int sym_den
   zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
 }
 
-// The same group quantiser for values that are fetched on demand (x(i) returns element i; it is
-// called twice per element: once for the range, once for the codes), so that no array of G
-// values has to live in registers.  Same operations in the same order as quantize_group.
-template <int G, int BITS, typename Fetch>
-__device__ inline void quantize_group_streamed(Fetch x, int mode, int sym_den_literal,
-                                               uint32_t (&words)[G * BITS / 32], __half& scale, __half& zero) {
-  constexpr int W = G * BITS / 32;
-  constexpr int QMAX = (1 << BITS) - 1;
-  constexpr int HALF = 1 << (BITS - 1);
-  constexpr int LB = BITS == 3 ? 2 : BITS;             // field width of the (low) plane
-  constexpr int FPW = 32 / LB;                         // fields per word of it
-  const float x0 = x(0);
-  float mn = x0, mx = x0, am = fabsf(x0);
-  for (int i = 1; i < G; ++i) {
-    const float v = x(i);
-    mn = fminf(mn, v);
-    mx = fmaxf(mx, v);
-    am = fmaxf(am, fabsf(v));
-  }
-  const float den = sym_den_literal ? (float)QMAX : (float)(HALF - 1);
-  const __half Sa = __float2half_rn((mx - mn) / (float)QMAX);
-  const __half Ss = __float2half_rn(am / den);
-  const float Saf = h2f(Sa), Ssf = h2f(Ss);
-  const float rSa = group_reciprocal(Saf), rSs = group_reciprocal(Ssf);
-  uint32_t wa[W], ws[W];
-#pragma unroll
-  for (int i = 0; i < W; ++i) { wa[i] = 0u; ws[i] = 0u; }
-  float ea = 0.f, es = 0.f;
-  // word by word (static indices into wa / ws), fields in index order inside each word
-#pragma unroll
-  for (int w = 0; w < G / FPW; ++w) {
-    uint32_t la = 0u, ls = 0u, ha = 0u, hs = 0u;
-    for (int f = 0; f < FPW; ++f) {
-      const int i = w * FPW + f;
-      const float v = x(i);
-      const float ca = __builtin_amdgcn_fmed3f(rintf(code_quotient(v - mn, Saf, rSa)), 0.f, (float)QMAX);
-      const float cs = __builtin_amdgcn_fmed3f(rintf(code_quotient(v, Ssf, rSs)), (float)(-HALF), (float)(HALF - 1));
-      const float ra = Saf * ca + mn;
-      const float rs = Ssf * cs;
-      ea = ea + fabsf(v - ra);
-      es = es + fabsf(v - rs);
-      const uint32_t ua = (uint32_t)(int)ca, us = (uint32_t)((int)cs + HALF);
-      if constexpr (BITS == 3) {
-        la |= (ua & 3u) << (f * 2);
-        ls |= (us & 3u) << (f * 2);
-        ha |= (ua >> 2) << f;
-        hs |= (us >> 2) << f;
-      } else {
-        la |= ua << (f * BITS);
-        ls |= us << (f * BITS);
-      }
-    }
-    wa[w] = la;
-    ws[w] = ls;
-    if constexpr (BITS == 3) {                         // 16 high bits per low word: two low words share one
-      wa[G / 16 + w / 2] |= ha << (16 * (w % 2));
-      ws[G / 16 + w / 2] |= hs << (16 * (w % 2));
-    }
-  }
-  const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
-#pragma unroll
-  for (int i = 0; i < W; ++i) words[i] = asym ? wa[i] : ws[i];
-  scale = asym ? __hneg(Sa) : Ss;
-  zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
+// Element i of a group kept as packed fp16 pairs.
+template <int N>
+__device__ inline float packed_half(const uint32_t (&xp)[N], int i) {
+  const uint32_t w = xp[i / 2];
+  return h2f(__ushort_as_half((unsigned short)((i & 1) ? (w >> 16) : (w & 0xffffu))));
 }
 
 // The same group quantiser spread over 8 neighbouring lanes (lane `sub` of the group holds the
@@ -348,14 +292,24 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
 #pragma unroll
         for (int i = 0; i < G; ++i) x[i] = h2f(scaled_half(x[i], inv[i]));
       }
-      quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+      quantize_group<G, BITS>([&](int i) { return x[i]; }, j.mode, a.sym_den_literal, words, s, z);
     } else {
-      auto fetch = [&](int i) -> float {
-        float v = h2f(src[i]);
-        if (norm) v = h2f(scaled_half(v, inv[i]));
-        return v;
-      };
-      quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+      // 64 floats do not fit the register file next to the rest: the group stays packed as fp16 pairs
+      uint32_t xp[G / 2];
+#pragma unroll
+      for (int p = 0; p < G / 8; ++p) {
+        const uint4 raw = reinterpret_cast<const uint4*>(src)[p];
+        xp[4 * p] = raw.x; xp[4 * p + 1] = raw.y; xp[4 * p + 2] = raw.z; xp[4 * p + 3] = raw.w;
+      }
+      if (norm) {
+#pragma unroll
+        for (int p = 0; p < G / 2; ++p) {
+          const uint32_t lo = __half_as_ushort(scaled_half(packed_half(xp, 2 * p), inv[2 * p]));
+          const uint32_t hi = __half_as_ushort(scaled_half(packed_half(xp, 2 * p + 1), inv[2 * p + 1]));
+          xp[p] = lo | (hi << 16);
+        }
+      }
+      quantize_group<G, BITS>([&](int i) { return packed_half(xp, i); }, j.mode, a.sym_den_literal, words, s, z);
     }
     // a row is one plane of LB-bit fields over all channels (3-bit: followed by the plane of high bits)
     constexpr int LB = BITS == 3 ? 2 : BITS;
@@ -429,28 +383,34 @@ __device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j
       if constexpr (G <= 32) {
         float x[G];
 #pragma unroll
-        for (int i = 0; i < G; ++i) x[i] = fetch(i);
-        quantize_group<G, BITS>(x, j.mode, a.sym_den_literal, words, s, z);
+        for (int i = 0; i < G; ++i) x[i] = h2f(fetch(i));
+        quantize_group<G, BITS>([&](int i) { return x[i]; }, j.mode, a.sym_den_literal, words, s, z);
       } else {
-        // 64 values do not fit the register file next to the rest: fetch each element twice
-        quantize_group_streamed<G, BITS>(fetch, j.mode, a.sym_den_literal, words, s, z);
+        // 64 floats do not fit the register file next to the rest: the group stays packed as fp16 pairs
+        uint32_t xp[G / 2];
+#pragma unroll
+        for (int p = 0; p < G / 2; ++p) {
+          const uint32_t lo = __half_as_ushort(fetch(2 * p)), hi = __half_as_ushort(fetch(2 * p + 1));
+          xp[p] = lo | (hi << 16);
+        }
+        quantize_group<G, BITS>([&](int i) { return packed_half(xp, i); }, j.mode, a.sym_den_literal, words, s, z);
       }
     };
     const long long t0 = a.w_sink + tg * G;              // first token of the group
     if (t0 >= a.n_old) {
       // the whole group comes from x_new (bulk calls): one base address, a fixed stride
       const __half* src0 = j.x_new + ((bh * a.t_new) + (t0 - a.n_old)) * kHeadDim + c;
-      run([&](int i) -> float {
-        float v = h2f(src0[i * kHeadDim]);
-        if (j.normalise) v = h2f(scaled_half(v, inv));
+      run([&](int i) -> __half {
+        __half v = src0[i * kHeadDim];
+        if (j.normalise) v = scaled_half(h2f(v), inv);
         return v;
       });
     } else {
-      run([&](int i) -> float {
+      run([&](int i) -> __half {
         bool from_new;
         const __half* src = token_row(j, a, bh, t0 + i, from_new);
-        float v = h2f(src[c]);
-        if (from_new && j.normalise) v = h2f(scaled_half(v, inv));
+        __half v = src[c];
+        if (from_new && j.normalise) v = scaled_half(h2f(v), inv);
         return v;
       });
     }
