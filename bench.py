@@ -41,6 +41,9 @@ def parse():
     p.add_argument("--instances", type=int, default=8, help="distinct caches rotated through the timed steps")
     p.add_argument("--layers", type=int, default=None, help="layers per step (default: the workload's)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--inner-kernel", type=int, default=0, choices=[0, 1],
+                   help="0: the default fused kernel (4x4x4 fp16 matrix instructions); 1: the fp8 x fp4 "
+                        "block-scaled kernel for 2-bit caches (comparison runs)")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
     p.add_argument("--asym-frac", type=float, default=None, metavar="F",
                    help="fill the caches with crafted groups of which a fraction F is quantised asymmetrically "
@@ -241,6 +244,7 @@ def main():
         w = w.with_(k_mode=modes[args.k_mode])
     if args.v_mode:
         w = w.with_(v_mode=modes[args.v_mode])
+    iq.innerq_select_inner_kernel(args.inner_kernel)
     kind_id = {"inner": iq.KIND_INNER, "outer": iq.KIND_OUTER, "fp16": iq.KIND_FP16}[args.kind]
     n_layers = args.layers or w.n_layers
     K, W = args.steps, args.warmup
@@ -378,7 +382,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "kind": args.kind, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
+        "config": {"workload": w.name, "kind": args.kind, "inner_kernel": args.inner_kernel, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
                    "v_bits": args.v_bits or w.bits,
                    **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}

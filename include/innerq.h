@@ -205,6 +205,15 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
  * cancels a pending request. */
 int innerq_profile_next_attention(void *ev_start, void *ev_stop);
 
+/* Measurement switch (no counterpart in the paper).  2-bit inner-grouped caches have a second
+ * fused kernel that computes the same partial results: it forms the inner sums over the stored
+ * fields with the block-scaled fp8 x fp4 matrix instruction (2-bit keys and values, at most 4
+ * query heads per kv head) instead of 4x4x4 fp16 matrix instructions.  It is slower on the
+ * measured configurations and off by default.  which = 0: every configuration on the 4x4x4 form
+ * (default); which = 1: the fp8 x fp4 form where it applies, for side-by-side timing and parity
+ * runs.  Process-wide, host-side only; returns INNERQ_E_ARG for any other value. */
+int innerq_select_inner_kernel(int which);
+
 /* Measurement yardstick (no counterpart in the paper): a plain read-only streaming kernel
  * over `bytes` bytes of device memory at `data` (16-byte aligned, bytes a multiple of 16),
  * launched on hip_stream.  It gives the rate a pure HBM read of that size reaches on this

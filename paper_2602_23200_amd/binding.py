@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.innerq_decode_attention.restype = C.c_int
         L.innerq_profile_next_attention.argtypes = [C.c_void_p, C.c_void_p]
         L.innerq_profile_next_attention.restype = C.c_int
+        L.innerq_select_inner_kernel.argtypes = [C.c_int]
+        L.innerq_select_inner_kernel.restype = C.c_int
         L.innerq_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.innerq_stream_read_probe.restype = C.c_int
         _lib = L
@@ -200,6 +202,13 @@ def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, 
 def innerq_profile_next_attention(ev_start: Optional[int], ev_stop: Optional[int]) -> None:
     """ev_start / ev_stop: raw hipEvent_t handles (ints), or None to cancel."""
     lib().innerq_profile_next_attention(ev_start, ev_stop)
+
+
+def innerq_select_inner_kernel(which: int) -> None:
+    """0: 4x4x4 fp16 fused kernel everywhere (default); 1: the fp8 x fp4 kernel for 2-bit caches where it applies."""
+    st = lib().innerq_select_inner_kernel(which)
+    if st != OK:
+        raise InnerQError(st, "innerq_select_inner_kernel")
 
 
 def innerq_stream_read_probe(data, sink, ev_start: Optional[int] = None, ev_stop: Optional[int] = None,

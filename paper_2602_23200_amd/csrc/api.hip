@@ -111,6 +111,12 @@ int innerq_profile_next_attention(void* ev_start, void* ev_stop) {
   return INNERQ_OK;
 }
 
+int innerq_select_inner_kernel(int which) {
+  if (which != 0 && which != 1) return INNERQ_E_ARG;
+  g_inner_variant = which;
+  return INNERQ_OK;
+}
+
 int innerq_validate_config(const innerq_config_t* cfg) { return check_config(cfg); }
 
 const char* innerq_status_string(int status) {

@@ -652,7 +652,10 @@ struct LaunchFn {
   hipError_t operator()() const { return launch_t<KB, VB, G>(a, n_both, n_splits, win, L); }
 };
 
+int g_inner_variant = 0;
+
 int attention_inner_waves_per_cu(const AttnArgs& a) {
+  if (g_inner_variant == 1 && attention_inner_f4_supported(a)) return attention_inner_f4_waves_per_cu(a);
   // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
   static int cache[4][2][2][2][2] = {};
   const int r = a.n_q_heads / a.n_kv_heads;
@@ -666,6 +669,8 @@ int attention_inner_waves_per_cu(const AttnArgs& a) {
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!attention_inner_supported(a)) return hipErrorInvalidValue;
+  if (g_inner_variant == 1 && attention_inner_f4_supported(a))
+    return launch_attention_inner_f4(a, n_both_ll, n_splits, win, stream, ev_start, ev_stop);
   const Launch L = {stream, ev_start, ev_stop};
   return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});
 }

@@ -127,6 +127,16 @@ struct Launch { hipStream_t stream; hipEvent_t ev_start, ev_stop; };
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
+// The same partial results for 2-bit codes from the block-scaled fp8 x fp4 matrix instruction
+// (128-token tiles).  Parity-green but slower than the 4x4x4 form (see the file header), so it runs
+// only on request: launch_attention_inner and attention_inner_waves_per_cu route to it when
+// g_inner_variant == 1 and it applies.
+bool attention_inner_f4_supported(const AttnArgs& a);
+int attention_inner_f4_waves_per_cu(const AttnArgs& a);
+hipError_t launch_attention_inner_f4(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
+                                     hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+extern int g_inner_variant;   // 0: 4x4x4 fp16 form everywhere (default); 1: fp8 x fp4 form where it applies
+
 // Comparison kernel over an unquantised fp16 store, same launch shape.
 bool attention_fp16_supported(const AttnArgs& a);
 int attention_fp16_waves_per_cu(const AttnArgs& a);

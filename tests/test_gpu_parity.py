@@ -490,3 +490,71 @@ def test_random_configurations(env, i):
     g, got = run_attention(torch, iq, o, K, V, q)
     assert_cache_equal(g, want_cache, o, what=str(kw))
     assert max_rel_err(got, want) <= TOL, (kw, v_bits)
+
+
+# ---------------------------------------------------------------------------
+# The second fused kernel for 2-bit caches (block-scaled fp8 x fp4 matrix instruction, off by
+# default): same oracle, same tolerance.
+# ---------------------------------------------------------------------------
+@pytest.fixture
+def f4_kernel(env):
+    _, iq = env
+    iq.innerq_select_inner_kernel(1)
+    yield
+    iq.innerq_select_inner_kernel(0)
+
+
+@pytest.mark.parametrize("group,k_mode,v_mode", [(32, orc.HYBRID, orc.HYBRID), (64, orc.HYBRID, orc.HYBRID),
+                                                  (32, orc.SYM, orc.SYM), (64, orc.SYM, orc.HYBRID),
+                                                  (32, orc.ASYM, orc.SYM)])
+@pytest.mark.parametrize("n_tokens", [181, 308, 1237, 2900])
+def test_fp4_kernel_small(env, f4_kernel, group, k_mode, v_mode, n_tokens):
+    """One tile, ragged tiles (the quantised range is no multiple of 128), several splits."""
+    torch, iq = env
+    w = small(bits=2, group=group, k_mode=k_mode, v_mode=v_mode, n_tokens=n_tokens)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("heads", [(4, 4), (2, 1), (12, 4), (3, 1)])
+def test_fp4_kernel_head_ratios_and_key_norm(env, f4_kernel, heads):
+    """Fewer than four query heads per kv head (empty operand rows), and the query rescaled by the
+    key norm inside the kernel."""
+    torch, iq = env
+    hq, hk = heads
+    w = small(n_q_heads=hq, n_kv_heads=hk, n_tokens=900)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    q = wl.query(w)
+    norm, inv = orc.calibrate_key_norm(K, per_head=True)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V, k_inv_norm=inv), q, q_scale=norm)
+    _, got = run_attention(torch, iq, o, K, V, q, k_inv_norm=inv, q_scale=norm)
+    assert max_rel_err(got, want) <= TOL
+
+
+def test_fp4_kernel_extreme_queries(env, f4_kernel):
+    """Queries whose heads differ in magnitude by many binades (the per-head power-of-two scaling of
+    the fp8 operand), a zero head, and one dominant key (the reference level of the softmax rises)."""
+    torch, iq = env
+    w = small(n_tokens=1500)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    K = K.copy()
+    K[:, :, 777] *= np.float16(6.0)
+    q = wl.query(w).copy()
+    q[:, 0] *= np.float16(2.0 ** -12)
+    q[:, 1] *= np.float16(24.0)
+    q[:, 2] = 0
+    q[:, 3, :64] = 0
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
+def test_fp4_kernel_full_size_sampled(env, f4_kernel):
+    test_attention_baseline_configs_full_size_sampled(env, "llama3_8b_32k", [(0, 0), (7, 7)])
+    test_attention_baseline_configs_full_size_sampled(env, "mistral_7b_8k", [(31, 7)])
