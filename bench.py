@@ -29,8 +29,9 @@ HBM_PEAK_GBS = 8000.0
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=200)
-    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--steps", type=int, default=400)
+    p.add_argument("--warmup", type=int, default=400,
+                   help="untimed steps first (the device needs some 10 ms of load before its clocks settle)")
     p.add_argument("--workload", default="llama3_8b_32k")
     p.add_argument("--kind", default="inner", choices=["inner", "outer", "fp16"])
     p.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="code width (default: the workload's)")
@@ -41,6 +42,11 @@ def parse():
     p.add_argument("--instances", type=int, default=8, help="distinct caches rotated through the timed steps")
     p.add_argument("--layers", type=int, default=None, help="layers per step (default: the workload's)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--step-mode", default="fused", choices=["fused", "serial", "two-stream"],
+                   help="fused (default): innerq_decode_step, i.e. attention over the cache plus the new token, then "
+                        "one launch that merges the partials, appends the token and quantises one step ahead; "
+                        "serial: innerq_quantize_append, then innerq_decode_attention (three launches); two-stream: "
+                        "the deferred append on a side stream next to the attention")
     p.add_argument("--inner-kernel", type=int, default=0, choices=[0, 1],
                    help="0: the default fused kernel (4x4x4 fp16 matrix instructions); 1: the fp8 x fp4 "
                         "block-scaled kernel for 2-bit caches (comparison runs)")
@@ -66,6 +72,14 @@ class Hip:
         self.rt.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.rt.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         self.rt.hipEventDestroy.argtypes = [C.c_void_p]
+        self.rt.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.rt.hipStreamWaitEvent.argtypes = [C.c_void_p, C.c_void_p, C.c_uint]
+
+    def record(self, ev: int, stream: int) -> None:
+        assert self.rt.hipEventRecord(ev, stream) == 0
+
+    def wait(self, stream: int, ev: int) -> None:
+        assert self.rt.hipStreamWaitEvent(stream, ev, 0) == 0
 
     def event(self) -> int:
         e = C.c_void_p()
@@ -250,7 +264,7 @@ def main():
     K, W = args.steps, args.warmup
     # one cache per layer; single-layer workloads rotate `instances` caches instead
     n_inst = n_layers if n_layers > 1 else max(1, args.instances)
-    per_inst_appends = -(-(K + W + 2 * K) // n_inst) + 1 if n_layers == 1 else (K + W + 2 * K) + 1
+    per_inst_appends = -(-(K + W + 3 * K) // n_inst) + 2 if n_layers == 1 else (K + W + 3 * K) + 2
     cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
     cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
                          w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits)
@@ -284,7 +298,7 @@ def main():
 
     state = {"i": 0}
 
-    def step(profile=None):
+    def step_serial(profile=None):
         """One decode step: every layer appends its new token and attends."""
         for layer in range(n_layers):
             i = state["i"]
@@ -294,6 +308,52 @@ def main():
             if profile is not None:
                 iq.innerq_profile_next_attention(*profile[layer])
             iq.innerq_decode_attention(cache, q_new[i % pool], ws, out=out, stream=stream)
+
+    hip = Hip()
+    side = torch.cuda.Stream()
+    main_h, side_h = stream.cuda_stream, side.cuda_stream
+    ev_ready = [hip.event() for _ in range(4)]                 # inputs of a step are ready (main stream)
+    ev_done = [hip.event() for _ in range(n_inst)]             # side work on cache instance j is done
+    pending = [False] * n_inst
+
+    def step_overlapped(profile=None):
+        """The same work per layer, the append off the critical path: attention over the cache plus the
+        new token (read from its input) on the main stream; window copy and the quantisation the next
+        step needs on the side stream, ordered by events."""
+        for layer in range(n_layers):
+            i = state["i"]
+            state["i"] += 1
+            j = i % n_inst
+            cache = caches[j]
+            ready = ev_ready[i % 4]
+            hip.record(ready, main_h)
+            if pending[j]:
+                hip.wait(main_h, ev_done[j])                   # this cache's previous append has finished
+            if profile is not None:
+                iq.innerq_profile_next_attention(*profile[layer])
+            iq.innerq_decode_attention_next(cache, k_new[i % pool], v_new[i % pool], q_new[i % pool], ws, out=out,
+                                            stream=stream)
+            hip.wait(side_h, ready)
+            iq.innerq_append_deferred(cache, k_new[i % pool], v_new[i % pool], stream=side)
+            hip.record(ev_done[j], side_h)
+            pending[j] = True
+
+    def step_fused(profile=None):
+        """The same work per layer in two launches: attention (new token read from its input), then
+        merge + append + quantisation one step ahead."""
+        for layer in range(n_layers):
+            i = state["i"]
+            state["i"] += 1
+            if profile is not None:
+                iq.innerq_profile_next_attention(*profile[layer])
+            iq.innerq_decode_step(caches[i % n_inst], k_new[i % pool], v_new[i % pool], q_new[i % pool], ws, out=out,
+                                  stream=stream)
+
+    overlapped = args.step_mode != "serial"
+    if overlapped:
+        for cache in caches:
+            iq.innerq_quantize_ahead(cache, stream=stream)
+    step = {"fused": step_fused, "serial": step_serial, "two-stream": step_overlapped}[args.step_mode]
 
     for _ in range(W):
         step()
@@ -307,7 +367,6 @@ def main():
     n_ctx_end = caches[0].n_tokens
 
     # second pass of K steps with HIP events around the dominant kernel of every attention call
-    hip = Hip()
     evs = [[(hip.event(), hip.event()) for _ in range(n_layers)] for _ in range(K)]
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -341,6 +400,9 @@ def main():
 
     attn_ms = time_only(attn_only, K) * n_layers
     append_ms = time_only(append_only, K) * n_layers
+    # the other step mode, for the breakdown (the serial calls also work on caches that were run ahead)
+    torch.cuda.synchronize()
+    other_ms = time_only(step_serial, K) if overlapped else None
 
     per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
     alg_bytes = per_unit * units
@@ -372,17 +434,19 @@ def main():
         traffic = int(m.group(1)) if m else None
 
     result = {
-        "metric": "decode-attention tokens/s (one attention layer step: quantize_append + decode_attention, "
-                  "2-bit/4-bit inner-grouped KV) + achieved HBM GB/s of the fused kernel (% of peak)"
+        "metric": "decode-attention tokens/s (one attention layer step: append of the new token with its quantisation "
+                  "+ decode attention, 2-bit/4-bit inner-grouped KV) + achieved HBM GB/s of the fused kernel (% of peak)"
                   if n_layers == 1 else
-                  "decode tokens/s over all layers (quantize_append + decode_attention per layer) + achieved HBM GB/s",
+                  "decode tokens/s over all layers (append with quantisation + decode attention per layer) + "
+                  "achieved HBM GB/s",
         "value": B / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "kind": args.kind, "inner_kernel": args.inner_kernel, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
+        "config": {"workload": w.name, "kind": args.kind, "inner_kernel": args.inner_kernel,
+                   "step_mode": args.step_mode, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
                    "v_bits": args.v_bits or w.bits,
                    **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}
@@ -400,7 +464,7 @@ def main():
                                                    "frac_of_peak": stream_gbs / HBM_PEAK_GBS,
                                                    "kernel_frac_of_it": achieved / stream_gbs}},
         "breakdown_ms": {"step": ms_per_step, "step_with_events": (t3 - t2) / K * 1e3,
-                         "attention_only": attn_ms, "append_only": append_ms},
+                         "attention_only": attn_ms, "append_only": append_ms, "step_serial": other_ms},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, kind_id, args.cpu_seconds, args.v_bits)

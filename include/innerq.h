@@ -194,6 +194,52 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Quantisation off the critical path of a decode step (the paper names this as future work at
+ * the end of its Section "Latency": the quantisation of evicted tokens can be overlapped with
+ * attention).  What leaves the recent windows at step t + 1 is already known at step t, and
+ * the packed form of a token (or of a group of G tokens) depends on its own values only, so
+ * it can be written to the store one step early, into rows that no attention call reads before
+ * they become valid.  Three calls; the results (outputs and cache contents) are those of
+ * innerq_quantize_append followed by innerq_decode_attention, bit for bit in the cache.
+ *
+ * innerq_quantize_ahead: writes to the store what a single-token append to the current
+ *   cache would evict (one key token; one group of values if that append completes a group).
+ *   n_tokens does not change.  Call once after the prompt has been appended, before the first
+ *   innerq_decode_attention_next.  Idempotent.
+ * innerq_decode_attention_next: attention for the query of the NEXT token over the
+ *   n_tokens + 1 tokens formed by the cache and that token, whose key and value rows are read
+ *   from k_new / v_new (device, fp16 [B][Hk][1][d], keys already normalised if a key norm is
+ *   in use) instead of the ring.  Requires that the store already holds what the append of
+ *   that token evicts (innerq_quantize_ahead, or the previous innerq_append_deferred).
+ *   Does not modify the cache.  Other arguments as innerq_decode_attention.
+ * innerq_append_deferred: copies the new token into its window, n_tokens += 1, and does
+ *   the innerq_quantize_ahead work for the step after.  It reads the rings and writes one
+ *   ring slot and store rows that innerq_decode_attention_next of the same step does not
+ *   touch, so the two may run concurrently on different streams: with the attention call on
+ *   the main stream and this call on a side stream, a step's critical path is the attention
+ *   alone.  Ordering the caller must provide (events): this call after k_new / v_new are
+ *   ready and after the previous innerq_append_deferred; the NEXT step's attention after this
+ *   call.
+ * (w_recent >= 1, which every configuration satisfies, is what makes this possible: the newest
+ * token is never quantised in the step that appends it.)  innerq_decode_attention_next and
+ * innerq_append_deferred return INNERQ_E_CAPACITY when the cache is full. */
+int innerq_quantize_ahead(const innerq_config_t *cfg, innerq_cache_t *cache, void *hip_stream);
+int innerq_decode_attention_next(const innerq_config_t *cfg, const innerq_cache_t *cache,
+                                 const void *k_new, const void *v_new, const void *q_fp16,
+                                 const float *q_scale, void *out, int out_is_fp32, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+int innerq_append_deferred(const innerq_config_t *cfg, innerq_cache_t *cache, const void *k_new,
+                           const void *v_new, void *hip_stream);
+
+/* One decode step in two launches instead of three: innerq_decode_attention_next followed by
+ * innerq_append_deferred on the same stream, with the log-sum-exp merge of the attention call
+ * and the append sharing one launch (they touch disjoint memory).  Same preconditions, results
+ * and errors as those two calls; on success n_tokens += 1 and the store already holds what the
+ * next step evicts. */
+int innerq_decode_step(const innerq_config_t *cfg, innerq_cache_t *cache, const void *k_new,
+                       const void *v_new, const void *q_fp16, const float *q_scale, void *out,
+                       int out_is_fp32, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Measurement hook (no counterpart in the paper; its Section "Latency" times the fused
  * dequantise-and-multiply kernels on their own, and this lets a benchmark do the same).
  * The next innerq_decode_attention call made by the calling host thread attaches

@@ -73,6 +73,16 @@ def lib() -> C.CDLL:
         L.innerq_decode_attention.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.innerq_decode_attention.restype = C.c_int
+        L.innerq_quantize_ahead.argtypes = [cfgp, cachep, C.c_void_p]
+        L.innerq_quantize_ahead.restype = C.c_int
+        L.innerq_decode_attention_next.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.innerq_decode_attention_next.restype = C.c_int
+        L.innerq_decode_step.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.innerq_decode_step.restype = C.c_int
+        L.innerq_append_deferred.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.innerq_append_deferred.restype = C.c_int
         L.innerq_profile_next_attention.argtypes = [C.c_void_p, C.c_void_p]
         L.innerq_profile_next_attention.restype = C.c_int
         L.innerq_select_inner_kernel.argtypes = [C.c_int]
@@ -197,6 +207,60 @@ def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, 
     if st != OK:
         raise InnerQError(st, "innerq_decode_attention")
     return out
+
+
+def innerq_quantize_ahead(cache: Cache, stream=None) -> None:
+    """Writes to the store what the next single-token append will evict (n_tokens unchanged)."""
+    st = lib().innerq_quantize_ahead(C.byref(cache.cfg), C.byref(cache.c), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_quantize_ahead")
+
+
+def innerq_decode_attention_next(cache: Cache, k_new, v_new, q, workspace, out=None, q_scale=None, stream=None):
+    """Attention over the cache plus one token whose rows are k_new, v_new (fp16 [B, Hk, 1, d]), not yet appended."""
+    import torch
+    for t in (k_new, v_new, q):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert k_new.shape == v_new.shape and k_new.shape[2] == 1
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    assert out.is_contiguous() and out.dtype in (torch.float32, torch.float16)
+    st = lib().innerq_decode_attention_next(C.byref(cache.cfg), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+                                            q.data_ptr(), _ptr(q_scale), out.data_ptr(),
+                                            int(out.dtype == torch.float32), workspace.data_ptr(),
+                                            workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_decode_attention_next")
+    return out
+
+
+def innerq_decode_step(cache: Cache, k_new, v_new, q, workspace, out=None, q_scale=None, stream=None):
+    """innerq_decode_attention_next + innerq_append_deferred in two launches (merge and append share one)."""
+    import torch
+    for t in (k_new, v_new, q):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert k_new.shape == v_new.shape and k_new.shape[2] == 1
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    assert out.is_contiguous() and out.dtype in (torch.float32, torch.float16)
+    st = lib().innerq_decode_step(C.byref(cache.cfg), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+                                  q.data_ptr(), _ptr(q_scale), out.data_ptr(), int(out.dtype == torch.float32),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_decode_step")
+    return out
+
+
+def innerq_append_deferred(cache: Cache, k_new, v_new, stream=None) -> None:
+    """Copies the token k_new, v_new (fp16 [B, Hk, 1, d]) into its window and quantises one step ahead."""
+    import torch
+    for t in (k_new, v_new):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert k_new.shape == v_new.shape and k_new.shape[2] == 1
+    st = lib().innerq_append_deferred(C.byref(cache.cfg), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+                                      _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_append_deferred")
 
 
 def innerq_profile_next_attention(ev_start: Optional[int], ev_stop: Optional[int]) -> None:

@@ -77,6 +77,7 @@ TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which,
   v.zeros = uses_zeros(c, which) ? static_cast<const __half*>(which == 0 ? k.k_zeros : k.v_zeros) : nullptr;
   v.sink = static_cast<const __half*>(which == 0 ? k.k_sink : k.v_sink);
   v.ring = static_cast<const __half*>(which == 0 ? k.k_recent : k.v_recent);
+  v.newest = nullptr;
   v.form = form_of(c.kind, which);
   v.slots = ring_slots(c, which);
   v.n_sink = (int)p.n_sink;
@@ -185,18 +186,22 @@ int innerq_calibrate_key_norm(const innerq_config_t* cfg, const void* k_fp16, in
   return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
 }
 
-int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new,
-                           const void* v_new, int64_t t_new, const float* k_inv_norm, void* hip_stream) {
-  int st = check_config(cfg);
-  if (st != INNERQ_OK) return st;
-  st = check_cache(*cfg, cache);
-  if (st != INNERQ_OK) return st;
-  if (t_new < 0) return INNERQ_E_ARG;
-  if (t_new == 0) return INNERQ_OK;
-  if (!k_new || !v_new) return INNERQ_E_NULL;
-  if (misaligned(k_new) || misaligned(v_new) || (k_inv_norm && misaligned(k_inv_norm))) return INNERQ_E_ALIGN;
+}  // extern "C"
+
+// Appends t_new tokens (their window copies) and quantises the store rows between two states of the
+// cache: from the rows state `from` needs to the rows state `to` needs (a state = a token count).
+// The ordinary append has from = n_tokens, to = n_tokens + t_new; the deferred forms run one
+// token ahead.
+static int quantize_impl(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,
+                         int64_t t_new, const float* k_inv_norm, long long from, long long to, void* hip_stream,
+                         const AttnArgs* merge = nullptr) {
+  if (t_new > 0 && (!k_new || !v_new)) return INNERQ_E_NULL;
+  if ((k_new && misaligned(k_new)) || (v_new && misaligned(v_new)) || (k_inv_norm && misaligned(k_inv_norm)))
+    return INNERQ_E_ALIGN;
   const long long n0 = cache->n_tokens, n1 = n0 + t_new;
   if (n1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  if (to > cfg->capacity_tokens) to = cfg->capacity_tokens;
+  if (from > to) from = to;
 
   QuantArgs a;
   a.inv_norm = k_inv_norm;
@@ -216,40 +221,77 @@ int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, co
     j.mode = w == 0 ? cfg->k_mode : cfg->v_mode;
     j.slots = ring_slots(*cfg, w);
     // rows that leave the recent window during this call (oldest first)
-    j.row_begin = partition_of(*cfg, w, n0).n_quant;
-    j.row_end = partition_of(*cfg, w, n1).n_quant;
-    j.ring_from = cfg->w_sink + j.row_end;
+    j.row_begin = partition_of(*cfg, w, from).n_quant;
+    j.row_end = partition_of(*cfg, w, to).n_quant;
+    // new tokens from this index on stay in the recent ring at the end of this call
+    j.ring_from = cfg->w_sink + partition_of(*cfg, w, n1).n_quant;
     // per-token form: eight lanes share a group when the call is short (a decode step: the
     // dependent chain is what costs), one lane takes a whole group when there is bulk to fill the chip
     const long long groups = (long long)cfg->batch * cfg->n_kv_heads * (j.row_end - j.row_begin) * (kHeadDim / cfg->group);
     j.lanes = groups >= 4096 ? 1 : 8;
     j.normalise = (w == 0 && k_inv_norm) ? 1 : 0;
   }
-  const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream), merge);
   if (e != hipSuccess) return INNERQ_E_HIP;
   cache->n_tokens = n1;
   return INNERQ_OK;
 }
 
-int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* q_fp16,
-                            const float* q_scale, void* out, int out_is_fp32, void* workspace,
-                            size_t workspace_bytes, void* hip_stream) {
+extern "C" {
+
+int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new,
+                           const void* v_new, int64_t t_new, const float* k_inv_norm, void* hip_stream) {
   int st = check_config(cfg);
   if (st != INNERQ_OK) return st;
   st = check_cache(*cfg, cache);
   if (st != INNERQ_OK) return st;
+  if (t_new < 0) return INNERQ_E_ARG;
+  if (t_new == 0) return INNERQ_OK;
+  if (!k_new || !v_new) return INNERQ_E_NULL;
+  return quantize_impl(cfg, cache, k_new, v_new, t_new, k_inv_norm, cache->n_tokens, cache->n_tokens + t_new,
+                       hip_stream);
+}
+
+int innerq_quantize_ahead(const innerq_config_t* cfg, innerq_cache_t* cache, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  return quantize_impl(cfg, cache, nullptr, nullptr, 0, nullptr, cache->n_tokens, cache->n_tokens + 1, hip_stream);
+}
+
+int innerq_append_deferred(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,
+                           void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (!k_new || !v_new) return INNERQ_E_NULL;
+  return quantize_impl(cfg, cache, k_new, v_new, 1, nullptr, cache->n_tokens + 1, cache->n_tokens + 2, hip_stream);
+}
+
+}  // extern "C"
+
+// Attention over the first N tokens of the cache.  k_newest / v_newest (both or neither): fp16 rows
+// [B][Hk][d] of token N - 1 when that token has not been copied into its window yet.
+// defer_merge (may be null): the final merge is not launched; its arguments are returned instead.
+static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cache, long long N,
+                          const void* k_newest, const void* v_newest, const void* q_fp16, const float* q_scale,
+                          void* out, int out_is_fp32, void* workspace, size_t workspace_bytes, void* hip_stream,
+                          AttnArgs* defer_merge = nullptr) {
   if (!q_fp16 || !out || !workspace) return INNERQ_E_NULL;
   if (misaligned(q_fp16) || misaligned(out) || misaligned(workspace) || (q_scale && misaligned(q_scale)))
     return INNERQ_E_ALIGN;
-  if (cache->n_tokens < 1) return INNERQ_E_ARG;
+  if (N < 1) return INNERQ_E_ARG;
   if (workspace_bytes < innerq_workspace_bytes(cfg)) return INNERQ_E_WORKSPACE;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const innerq_config_t& c = *cfg;
-  const long long N = cache->n_tokens;
 
   AttnArgs a;
   a.k = view_of(c, *cache, 0, N);
   a.v = view_of(c, *cache, 1, N);
+  a.k.newest = static_cast<const __half*>(k_newest);
+  a.v.newest = static_cast<const __half*>(v_newest);
   a.q = static_cast<const __half*>(q_fp16);
   a.q_scale = q_scale;
   a.out = out; a.out_is_fp32 = out_is_fp32;
@@ -340,9 +382,64 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
     e = launch_attention_generic(a, 0, n_sink, win_b0, win_b1, n_win, n_splits, stream);
     if (e != hipSuccess) return INNERQ_E_HIP;
   }
+  if (defer_merge) {
+    *defer_merge = a;
+    return INNERQ_OK;
+  }
   e = launch_attention_merge(a, stream);
   return e == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
 }
+
+extern "C" {
+
+int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* q_fp16,
+                            const float* q_scale, void* out, int out_is_fp32, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  return attention_impl(cfg, cache, cache->n_tokens, nullptr, nullptr, q_fp16, q_scale, out, out_is_fp32, workspace,
+                        workspace_bytes, hip_stream);
+}
+
+int innerq_decode_attention_next(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* k_new,
+                                 const void* v_new, const void* q_fp16, const float* q_scale, void* out,
+                                 int out_is_fp32, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (!k_new || !v_new) return INNERQ_E_NULL;
+  if (misaligned(k_new) || misaligned(v_new)) return INNERQ_E_ALIGN;
+  if (cache->n_tokens + 1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  return attention_impl(cfg, cache, cache->n_tokens + 1, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
+                        workspace_bytes, hip_stream);
+}
+
+int innerq_decode_step(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,
+                       const void* q_fp16, const float* q_scale, void* out, int out_is_fp32, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (!k_new || !v_new) return INNERQ_E_NULL;
+  if (misaligned(k_new) || misaligned(v_new)) return INNERQ_E_ALIGN;
+  if (cache->n_tokens + 1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  AttnArgs merge;
+  st = attention_impl(cfg, cache, cache->n_tokens + 1, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
+                      workspace_bytes, hip_stream, &merge);
+  if (st != INNERQ_OK) return st;
+  // second launch: the merge of this step together with the append of its token and the
+  // quantisation the next step needs
+  return quantize_impl(cfg, cache, k_new, v_new, 1, nullptr, cache->n_tokens + 1, cache->n_tokens + 2, hip_stream,
+                       &merge);
+}
+
+}  // extern "C"
+
+extern "C" {
 
 int innerq_stream_read_probe(const void* data, size_t bytes, void* sink, void* hip_stream, void* ev_start,
                              void* ev_stop) {

@@ -32,6 +32,7 @@ struct TensorView {
   const __half* zeros;
   const __half* sink;
   const __half* ring;
+  const __half* newest;   // [B][Hk][d] rows of token n_tokens - 1 when it is not in the ring yet, else null
   int form;            // Form
   int bits;            // code width of this tensor
   int slots;           // ring slots
@@ -90,7 +91,10 @@ struct QuantArgs {
   long long capacity, n_old, t_new;
 };
 
-hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream);
+struct AttnArgs;
+// merge (may be null): the log-sum-exp merge of an attention call whose partials are complete on
+// this stream rides in the same launch (or, for the rare two-launch appends, goes first).
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream, const AttnArgs* merge = nullptr);
 hipError_t launch_calibrate(const __half* k, int batch, int n_kv_heads, long long n_tokens, int per_head,
                             float* norm_out, float* inv_out, hipStream_t stream);
 

@@ -5,6 +5,7 @@
 // multiply, add, subtract and divide below is a separate IEEE operation
 // (Section "Quantization Scheme", Eq. asym_quant; Figure "hybrid").
 #include "innerq_dev.h"
+#include "merge.h"
 
 namespace innerq {
 namespace {
@@ -457,8 +458,30 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
   else quantize_rows<G, 4>(a, j, idx);
 }
 
+// The same launch with the log-sum-exp merge of an attention call riding along: the first
+// merge_blocks work-groups (of job 0) merge four query heads each, the rest is quantize_kernel.
+// The two jobs touch disjoint memory (partials and output against store rows and window slots).
 template <int G>
-hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
+__global__ void __launch_bounds__(256) quantize_merge_kernel(QuantArgs a, long long copy_from, AttnArgs m,
+                                                             int merge_blocks) {
+  if ((int)blockIdx.x < merge_blocks) {
+    const long long bhq = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blockIdx.y == 0 && bhq < (long long)m.batch * m.n_q_heads) merge_head(m, bhq, threadIdx.x & 63);
+    return;
+  }
+  const QuantTensorJob& j = a.job[blockIdx.y];
+  const long long idx = (long long)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x;
+  if (copy_from >= 0 && idx >= copy_from) {
+    window_copy(a, j, idx - copy_from);
+    return;
+  }
+  if (j.bits == 2) quantize_rows<G, 2>(a, j, idx);
+  else if (j.bits == 3) quantize_rows<G, 3>(a, j, idx);
+  else quantize_rows<G, 4>(a, j, idx);
+}
+
+template <int G>
+hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream, const AttnArgs* merge) {
   const long long BH = (long long)a.batch * a.n_kv_heads;
   long long threads = 0;
   for (int w = 0; w < 2; ++w) {
@@ -486,6 +509,18 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream) {
     if (j.row_end > j.row_begin && a.w_sink + j.row_begin < a.n_old &&
         a.n_old + a.t_new - (a.w_sink + j.row_begin) > j.slots)
       disjoint = false;
+  }
+  if (merge && disjoint) {
+    // one launch: merge blocks first, then the quantise threads, then the window-copy threads
+    const long long qthreads = ((threads + 255) / 256) * 256;
+    const int merge_blocks = (int)(((long long)merge->batch * merge->n_q_heads + 3) / 4);
+    dim3 grid((unsigned)(merge_blocks + (qthreads + cthreads + 255) / 256), 2);
+    quantize_merge_kernel<G><<<grid, 256, 0, stream>>>(a, qthreads, *merge, merge_blocks);
+    return hipGetLastError();
+  }
+  if (merge) {
+    const hipError_t e = launch_attention_merge(*merge, stream);
+    if (e != hipSuccess) return e;
   }
   if (threads > 0 && disjoint) {
     const long long qthreads = ((threads + 255) / 256) * 256;
@@ -562,11 +597,11 @@ __global__ void norm_finalize_kernel(uint32_t* table, int n_kv_heads, int per_he
 
 }  // namespace
 
-hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream) {
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream, const AttnArgs* merge) {
   for (int w = 0; w < 2; ++w)
     if (a.job[w].form != kFp16 && (a.job[w].bits < 2 || a.job[w].bits > 4)) return hipErrorInvalidValue;
-  if (a.group == 32) return launch_quantize_t<32>(a, stream);
-  if (a.group == 64) return launch_quantize_t<64>(a, stream);
+  if (a.group == 32) return launch_quantize_t<32>(a, stream, merge);
+  if (a.group == 64) return launch_quantize_t<64>(a, stream, merge);
   return hipErrorInvalidValue;
 }
 

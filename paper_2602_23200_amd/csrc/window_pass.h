@@ -17,6 +17,7 @@ typedef float w_float4_t __attribute__((ext_vector_type(4)));
 // Element (token t, channel c) of one tensor of sequence-head bh, decoded per Eq. hybrid_dequant.
 __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, long long bh, long long t, int c) {
   constexpr int D = kHeadDim;
+  if (tv.newest && t == a.n_tokens - 1) return __half2float(tv.newest[bh * D + c]);
   if (t < tv.n_sink) return __half2float(tv.sink[(bh * a.w_sink + t) * D + c]);
   const long long row = t - a.w_sink;
   if (row >= tv.n_quant) return __half2float(tv.ring[(bh * tv.slots + (t % tv.slots)) * D + c]);
@@ -47,6 +48,7 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
 // fp16 row of token t if that tensor keeps it in fp16 (sink window, recent ring, fp16 store), else null.
 __device__ __forceinline__ const __half* fp16_row(const TensorView& tv, const AttnArgs& a, long long bh, long long t) {
   constexpr int D = kHeadDim;
+  if (tv.newest && t == a.n_tokens - 1) return tv.newest + bh * D;
   if (t < tv.n_sink) return tv.sink + (bh * a.w_sink + t) * D;
   const long long row = t - a.w_sink;
   if (row >= tv.n_quant) return tv.ring + (bh * tv.slots + (t % tv.slots)) * D;

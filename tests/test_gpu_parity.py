@@ -558,3 +558,145 @@ def test_fp4_kernel_extreme_queries(env, f4_kernel):
 def test_fp4_kernel_full_size_sampled(env, f4_kernel):
     test_attention_baseline_configs_full_size_sampled(env, "llama3_8b_32k", [(0, 0), (7, 7)])
     test_attention_baseline_configs_full_size_sampled(env, "mistral_7b_8k", [(31, 7)])
+
+
+# ---------------------------------------------------------------------------
+# Quantisation one step ahead (innerq_quantize_ahead / innerq_decode_attention_next /
+# innerq_append_deferred): every step equals the oracle's append followed by attention.
+# ---------------------------------------------------------------------------
+def _deferred_steps(torch, iq, o, K, V, Q, n_prompt, side_stream=None, fused=False):
+    """Runs tokens n_prompt .. N-1 through the deferred calls; returns the cache and the outputs."""
+    g = iq.allocate_cache(gpu_config(o))
+    Kd, Vd = to_dev(torch, K), to_dev(torch, V)
+    if n_prompt:
+        iq.innerq_quantize_append(g, Kd[:, :, :n_prompt].contiguous(), Vd[:, :, :n_prompt].contiguous())
+    iq.innerq_quantize_ahead(g)
+    ws = iq.allocate_workspace(g.cfg)
+    main = torch.cuda.current_stream()
+    outs, keep = [], []
+    done_prev = None
+    for t in range(n_prompt, K.shape[2]):
+        k_t, v_t = Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous()
+        q_t = to_dev(torch, Q[t - n_prompt])
+        keep.append((k_t, v_t, q_t))                  # alive until the side stream has used them
+        if fused:
+            outs.append(iq.innerq_decode_step(g, k_t, v_t, q_t, ws))
+        elif side_stream is None:
+            outs.append(iq.innerq_decode_attention_next(g, k_t, v_t, q_t, ws))
+            iq.innerq_append_deferred(g, k_t, v_t)
+        else:
+            ready = torch.cuda.Event()
+            ready.record(main)
+            if done_prev is not None:
+                main.wait_event(done_prev)            # this step's attention needs the previous step's side work
+            outs.append(iq.innerq_decode_attention_next(g, k_t, v_t, q_t, ws))
+            side_stream.wait_event(ready)
+            iq.innerq_append_deferred(g, k_t, v_t, stream=side_stream)
+            done_prev = torch.cuda.Event()
+            done_prev.record(side_stream)
+    torch.cuda.synchronize()
+    return g, [x.cpu().numpy() for x in outs]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("n_prompt,n_steps,group", [(0, 70, 32), (2, 100, 32), (50, 150, 32), (300, 140, 64)])
+def test_deferred_append_steps_match_oracle(env, kind, n_prompt, n_steps, group):
+    """From an empty or short cache through the sink window, the first eviction and several value
+    spills (w_sink 4, w_recent 48): outputs of every step and the final cache."""
+    torch, iq = env
+    w = small(n_tokens=n_prompt + n_steps, group=group)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((n_steps, w.batch, w.n_q_heads, w.head_dim)).astype(np.float16)
+    g, outs = _deferred_steps(torch, iq, o, K, V, Q, n_prompt)
+    # the ordinary calls on a second cache, step by step: the deferred outputs are the same bits
+    # (same kernels, same split plan; only the newest token's rows come from another address)
+    want_cache = orc.cache_new(o)
+    g_ref = iq.allocate_cache(gpu_config(o))
+    ws_ref = iq.allocate_workspace(g_ref.cfg)
+    Kd, Vd = to_dev(torch, K), to_dev(torch, V)
+    if n_prompt:
+        orc.quantize_append(o, want_cache, K[:, :, :n_prompt], V[:, :, :n_prompt])
+        iq.innerq_quantize_append(g_ref, Kd[:, :, :n_prompt].contiguous(), Vd[:, :, :n_prompt].contiguous())
+    for i, t in enumerate(range(n_prompt, n_prompt + n_steps)):
+        orc.quantize_append(o, want_cache, K[:, :, t:t + 1], V[:, :, t:t + 1])
+        iq.innerq_quantize_append(g_ref, Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous())
+        ref = iq.innerq_decode_attention(g_ref, to_dev(torch, Q[i]), ws_ref)
+        torch.cuda.synchronize()
+        assert np.array_equal(outs[i], ref.cpu().numpy()), f"step {i}"
+        if kind == orc.KIND_INNER and (i % 7 == 0 or i >= n_steps - 3):
+            want = orc.decode_attention(o, want_cache, Q[i])
+            assert max_rel_err(outs[i], want) <= TOL, f"step {i}"
+    assert_cache_equal(g, want_cache, o)
+    # the ordinary calls still work on such a cache (the rows written ahead are simply rewritten)
+    k1, v1 = K[:, :, -1:] * np.float16(0.5), V[:, :, -1:] * np.float16(2.0)
+    iq.innerq_quantize_append(g, to_dev(torch, k1), to_dev(torch, v1))
+    orc.quantize_append(o, want_cache, k1, v1)
+    ws = iq.allocate_workspace(g.cfg)
+    got = iq.innerq_decode_attention(g, to_dev(torch, Q[0]), ws)
+    torch.cuda.synchronize()
+    assert_cache_equal(g, want_cache, o)
+    assert max_rel_err(got.cpu().numpy(), orc.decode_attention(o, want_cache, Q[0])) <= TOL
+
+
+def test_deferred_append_on_a_side_stream(env):
+    """The deferred append of step t runs on a second stream next to the attention of step t
+    (and of step t + 1 up to the event): same outputs, same cache."""
+    torch, iq = env
+    n_prompt, n_steps = 2100, 200
+    w = small(n_tokens=n_prompt + n_steps, batch=4, n_q_heads=16, n_kv_heads=4)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    rng = np.random.default_rng(6)
+    Q = rng.standard_normal((n_steps, w.batch, w.n_q_heads, w.head_dim)).astype(np.float16)
+    side = torch.cuda.Stream()
+    g, outs = _deferred_steps(torch, iq, o, K, V, Q, n_prompt, side_stream=side)
+    g2, outs2 = _deferred_steps(torch, iq, o, K, V, Q, n_prompt)
+    for a_, b_ in zip(outs, outs2):
+        assert np.array_equal(a_, b_)
+    want_cache = orc.cache_init_prefill(o, K, V)
+    assert_cache_equal(g, want_cache, o)
+    want = orc.decode_attention(o, want_cache, Q[-1])
+    assert max_rel_err(outs[-1], want) <= TOL
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("n_prompt,n_steps,group", [(0, 120, 32), (300, 140, 64)])
+def test_decode_step_two_launches(env, kind, n_prompt, n_steps, group):
+    """innerq_decode_step (merge and append in one launch) against the separate deferred calls:
+    same outputs bit for bit, same cache as the oracle."""
+    torch, iq = env
+    w = small(n_tokens=n_prompt + n_steps, group=group)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    rng = np.random.default_rng(7)
+    Q = rng.standard_normal((n_steps, w.batch, w.n_q_heads, w.head_dim)).astype(np.float16)
+    g, outs = _deferred_steps(torch, iq, o, K, V, Q, n_prompt, fused=True)
+    _, outs2 = _deferred_steps(torch, iq, o, K, V, Q, n_prompt)
+    for i, (a_, b_) in enumerate(zip(outs, outs2)):
+        assert np.array_equal(a_, b_), f"step {i}"
+    want_cache = orc.cache_init_prefill(o, K, V)
+    assert g.n_tokens == n_prompt + n_steps
+    assert_cache_equal(g, want_cache, o)
+    if kind == orc.KIND_INNER:
+        assert max_rel_err(outs[-1], orc.decode_attention(o, want_cache, Q[-1])) <= TOL
+
+
+def test_deferred_calls_on_a_full_cache(env):
+    torch, iq = env
+    w = small(n_tokens=96)
+    o = oracle_config(w, capacity=96)
+    K, V = wl.kv_full(w)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K), to_dev(torch, V))
+    iq.innerq_quantize_ahead(g)                      # nothing left to write: accepted
+    ws = iq.allocate_workspace(g.cfg)
+    k1, v1, q = to_dev(torch, K[:, :, :1]), to_dev(torch, V[:, :, :1]), to_dev(torch, wl.query(w))
+    with pytest.raises(iq.InnerQError):
+        iq.innerq_decode_attention_next(g, k1, v1, q, ws)
+    with pytest.raises(iq.InnerQError):
+        iq.innerq_append_deferred(g, k1, v1)
+    with pytest.raises(iq.InnerQError):
+        iq.innerq_decode_step(g, k1, v1, q, ws)
+    assert g.n_tokens == 96
