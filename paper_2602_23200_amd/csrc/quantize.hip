@@ -458,19 +458,20 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
   else quantize_rows<G, 4>(a, j, idx);
 }
 
-// The same launch with the log-sum-exp merge of an attention call riding along: the first
-// merge_blocks work-groups (of job 0) merge four query heads each, the rest is quantize_kernel.
-// The two jobs touch disjoint memory (partials and output against store rows and window slots).
+// The same launch with the log-sum-exp merge of an attention call riding along: the last
+// merge_blocks work-groups (of job 0) merge four query heads each, the ones before them are
+// quantize_kernel (the longer dependent chain, so it is dispatched first).  The two jobs touch
+// disjoint memory (partials and output against store rows and window slots).
 template <int G>
 __global__ void __launch_bounds__(256) quantize_merge_kernel(QuantArgs a, long long copy_from, AttnArgs m,
-                                                             int merge_blocks) {
-  if ((int)blockIdx.x < merge_blocks) {
-    const long long bhq = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+                                                             int quant_blocks) {
+  if ((int)blockIdx.x >= quant_blocks) {
+    const long long bhq = (long long)(blockIdx.x - quant_blocks) * 4 + (threadIdx.x >> 6);
     if (blockIdx.y == 0 && bhq < (long long)m.batch * m.n_q_heads) merge_head(m, bhq, threadIdx.x & 63);
     return;
   }
   const QuantTensorJob& j = a.job[blockIdx.y];
-  const long long idx = (long long)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (copy_from >= 0 && idx >= copy_from) {
     window_copy(a, j, idx - copy_from);
     return;
@@ -511,11 +512,12 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream, const AttnA
       disjoint = false;
   }
   if (merge && disjoint) {
-    // one launch: merge blocks first, then the quantise threads, then the window-copy threads
+    // one launch: the quantise threads, the window-copy threads, then the merge blocks
     const long long qthreads = ((threads + 255) / 256) * 256;
     const int merge_blocks = (int)(((long long)merge->batch * merge->n_q_heads + 3) / 4);
-    dim3 grid((unsigned)(merge_blocks + (qthreads + cthreads + 255) / 256), 2);
-    quantize_merge_kernel<G><<<grid, 256, 0, stream>>>(a, qthreads, *merge, merge_blocks);
+    const int quant_blocks = (int)((qthreads + cthreads + 255) / 256);
+    dim3 grid((unsigned)(quant_blocks + merge_blocks), 2);
+    quantize_merge_kernel<G><<<grid, 256, 0, stream>>>(a, qthreads, *merge, quant_blocks);
     return hipGetLastError();
   }
   if (merge) {
