@@ -177,16 +177,30 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
       fs |= us << (i * BITS);
     }
   }
-  float ea = 0.f, es = 0.f;
-  const int first = (int)(threadIdx.x & 63u) & ~7;
+  // The two error sums in index order, as a relay over the 8 lanes: at stage s lane s of the group
+  // holds the sum of all elements before its own, adds its E elements one after the other and
+  // hands the result to lane s + 1 (one DPP shift).  Every lane runs every stage; only the stage
+  // that matches its position produces a value that is used.  Same additions in the same order as
+  // one lane summing all G values, 8 (E + 1) dependent steps instead of G cross-lane reads.
+  float ra_run = 0.f, rs_run = 0.f, ea = 0.f, es = 0.f;
 #pragma unroll
-  for (int l = 0; l < 8; ++l) {
+  for (int st = 0; st < 8; ++st) {
+    ea = ra_run;
+    es = rs_run;
 #pragma unroll
     for (int i = 0; i < E; ++i) {
-      ea = ea + __shfl(da[i], first + l);
-      es = es + __shfl(ds[i], first + l);
+      ea = ea + da[i];
+      es = es + ds[i];
+    }
+    if (st < 7) {
+      ra_run = lane_swap<0x111>(ea);                     // row_shr:1: lane j takes lane j - 1's value
+      rs_run = lane_swap<0x111>(es);
     }
   }
+  // lane 7 of the group now holds both totals: to all 8 lanes
+  const int last = ((int)(threadIdx.x & 63u) & ~7) + 7;
+  ea = __shfl(ea, last);
+  es = __shfl(es, last);
   const bool asym = (mode == INNERQ_ASYM) || (mode == INNERQ_HYBRID && ea < es);
   scale = asym ? __hneg(Sa) : Ss;
   zero = asym ? __float2half_rn(mn) : __float2half_rn(0.f);
@@ -209,7 +223,7 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
 
 // Where the fp16 row of token t (absolute index) of sequence-head bh lives when the quantiser
 // wants it: still in the recent ring if it was appended by an earlier call, else in x_new.
-__device__ inline const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
+__device__ __forceinline__ const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
                                           long long t, bool& from_new) {
   from_new = t >= a.n_old;
   if (from_new) return j.x_new + ((bh * a.t_new) + (t - a.n_old)) * kHeadDim;
@@ -229,7 +243,7 @@ __host__ __device__ inline CopySpan copy_span(const QuantArgs& a, const QuantTen
 
 // New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
 // ring -- unless this same call already moved them on to the quantised store.
-__device__ inline void window_copy(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
+__device__ __forceinline__ void window_copy(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
   constexpr int CPR = kHeadDim / 8;
   const long long BH = (long long)a.batch * a.n_kv_heads;
   // only the new tokens that stay in a window are visited: the first n_a (sink) and those from i_b on (ring)
@@ -254,13 +268,40 @@ __device__ inline void window_copy(const QuantArgs& a, const QuantTensorJob& j, 
   *reinterpret_cast<uint4*>(dst + ch * 8) = raw;
 }
 
+// Job y (0: keys, 1: values) of a launch, field by field: indexing the by-value kernel argument
+// with blockIdx.y makes the compiler copy the whole argument block to scratch first (so does any
+// function that takes the block by reference and is not inlined: hence the forced inlining of
+// quantize_rows, window_copy and token_row).
+__device__ __forceinline__ QuantTensorJob pick_job(const QuantArgs& a, int y) {
+  const QuantTensorJob& k = a.job[0];
+  const QuantTensorJob& v = a.job[1];
+  QuantTensorJob j;
+  j.codes = y ? v.codes : k.codes;
+  j.scales = y ? v.scales : k.scales;
+  j.zeros = y ? v.zeros : k.zeros;
+  j.sink = y ? v.sink : k.sink;
+  j.ring = y ? v.ring : k.ring;
+  j.x_new = y ? v.x_new : k.x_new;
+  j.form = y ? v.form : k.form;
+  j.mode = y ? v.mode : k.mode;
+  j.slots = y ? v.slots : k.slots;
+  j.bits = y ? v.bits : k.bits;
+  j.lanes = y ? v.lanes : k.lanes;
+  j.row_begin = y ? v.row_begin : k.row_begin;
+  j.row_end = y ? v.row_end : k.row_end;
+  j.ring_from = y ? v.ring_from : k.ring_from;
+  j.normalise = y ? v.normalise : k.normalise;
+  return j;
+}
+
 __global__ void __launch_bounds__(256) window_copy_kernel(QuantArgs a) {
-  window_copy(a, a.job[blockIdx.y], (long long)blockIdx.x * blockDim.x + threadIdx.x);
+  const QuantTensorJob j = pick_job(a, (int)blockIdx.y);
+  window_copy(a, j, (long long)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 // The quantise work of thread idx of tensor job j (keys and values may have different widths).
 template <int G, int BITS>
-__device__ inline void quantize_rows(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
+__device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTensorJob& j, long long idx) {
   const long long n_rows = j.row_end - j.row_begin;
   if (n_rows <= 0) return;
   const long long BH = (long long)a.batch * a.n_kv_heads;
@@ -447,7 +488,7 @@ __global__ void __launch_bounds__(256) quantize_kernel(QuantArgs a, long long co
   // Thread indices below copy_from quantise evicted tokens, those from copy_from on write the
   // new tokens into the windows (one launch; only used when no new token lands in a ring slot
   // that this call still has to read).  copy_from < 0: no copy work in this launch.
-  const QuantTensorJob& j = a.job[blockIdx.y];
+  const QuantTensorJob j = pick_job(a, (int)blockIdx.y);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (copy_from >= 0 && idx >= copy_from) {
     window_copy(a, j, idx - copy_from);
@@ -470,7 +511,7 @@ __global__ void __launch_bounds__(256) quantize_merge_kernel(QuantArgs a, long l
     if (blockIdx.y == 0 && bhq < (long long)m.batch * m.n_q_heads) merge_head(m, bhq, threadIdx.x & 63);
     return;
   }
-  const QuantTensorJob& j = a.job[blockIdx.y];
+  const QuantTensorJob j = pick_job(a, (int)blockIdx.y);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (copy_from >= 0 && idx >= copy_from) {
     window_copy(a, j, idx - copy_from);
