@@ -683,6 +683,37 @@ def test_decode_step_two_launches(env, kind, n_prompt, n_steps, group):
         assert max_rel_err(outs[-1], orc.decode_attention(o, want_cache, Q[-1])) <= TOL
 
 
+def test_decode_step_with_key_norm_and_fp16_output(env):
+    """Keys normalised by the caller before they are handed over, query rescaled inside the kernel
+    (q_scale), fp16 output: the oracle's append + attention with the same factors."""
+    torch, iq = env
+    n_prompt, n_steps = 400, 40
+    w = small(n_tokens=n_prompt + n_steps)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    norm, inv = orc.calibrate_key_norm(K[:, :, :n_prompt], per_head=True)
+    Kn = orc.apply_channel_scale(K, inv)
+    rng = np.random.default_rng(8)
+    Q = rng.standard_normal((n_steps, w.batch, w.n_q_heads, w.head_dim)).astype(np.float16)
+    g = iq.allocate_cache(gpu_config(o))
+    Kd, Vd = to_dev(torch, Kn), to_dev(torch, V)
+    iq.innerq_quantize_append(g, Kd[:, :, :n_prompt].contiguous(), Vd[:, :, :n_prompt].contiguous())
+    iq.innerq_quantize_ahead(g)
+    ws = iq.allocate_workspace(g.cfg)
+    scale = to_dev(torch, norm)
+    want_cache = orc.cache_init_prefill(o, Kn[:, :, :n_prompt], V[:, :, :n_prompt])
+    for i, t in enumerate(range(n_prompt, n_prompt + n_steps)):
+        out16 = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float16, device="cuda")
+        iq.innerq_decode_step(g, Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous(), to_dev(torch, Q[i]),
+                              ws, out=out16, q_scale=scale)
+        orc.quantize_append(o, want_cache, Kn[:, :, t:t + 1], V[:, :, t:t + 1])
+        if i % 5 == 0 or i == n_steps - 1:
+            torch.cuda.synchronize()
+            want = orc.decode_attention(o, want_cache, Q[i], q_scale=norm)
+            assert max_rel_err(out16.float().cpu().numpy(), want) <= TOL + 2.0 ** -10, f"step {i}"
+    assert_cache_equal(g, want_cache, o)
+
+
 def test_deferred_calls_on_a_full_cache(env):
     torch, iq = env
     w = small(n_tokens=96)
