@@ -18,8 +18,8 @@ SOURCES = {
     "quantize.hip": ["-ffp-contract=off"],
     "attention_generic.hip": [],
     "stream_probe.hip": [],
-    "attention_fp16.hip": ["-fno-honor-nans"],
-    "attention_outer.hip": ["-fno-honor-nans"],
+    "attention_fp16.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "attention_outer.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
     # no NaN canonicalisation around fmax; MFMA results straight into VGPRs
     "attention_inner.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
     "attention_inner_f4.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],

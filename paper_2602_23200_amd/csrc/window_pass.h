@@ -13,6 +13,8 @@ namespace innerq {
 typedef _Float16 w_half2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t w_u32x4 __attribute__((ext_vector_type(4)));
 typedef float w_float4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 w_half4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t w_u32x2 __attribute__((ext_vector_type(2)));
 
 // Element (token t, channel c) of one tensor of sequence-head bh, decoded per Eq. hybrid_dequant.
 __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, long long bh, long long t, int c) {
@@ -117,13 +119,18 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   __shared__ __attribute__((aligned(16))) _Float16 wq[NH][D];       // query, fp16 (exact)
   __shared__ __attribute__((aligned(16))) float wqf[KQ ? D : 1][NH];   // the same values as fp32, head fastest
   __shared__ __attribute__((aligned(16))) float wqs[NG][NH];        // their sums over each key group
-  __shared__ __attribute__((aligned(16))) float wp[64][NH];         // probabilities of the current 64 tokens
+  __shared__ __attribute__((aligned(16))) float wp[VQ ? 64 : 1][NH];   // probabilities of the current 64 tokens
+  // the same, rounded to fp16, as matrix operands: [token % 4][head][token / 4]
+  __shared__ __attribute__((aligned(16))) _Float16 wp16[VQ ? 1 : 4 * NH * 16];
 
   const int cg = lane & 15, tg = lane >> 4;
   auto token_of = [&](long long v) -> long long { return v < na ? v : b0 + (v - na); };
 
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;    // log2(e) / sqrt(d)
+  // o[h][e]: head h, channel 8 cg + e, the tokens 4 k + tg of every step.  Without packed value
+  // rows the same sums are held as matrix-instruction results oq[e][n] (heads 4 n .. 4 n + 3).
   float m_run[NH], l_run[NH], o[NH][8];
+  w_float4_t oq[8][NH4];
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
     m_run[h] = -INFINITY;
@@ -131,6 +138,10 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int n = 0; n < NH4; ++n) oq[e][n] = w_float4_t{0.f, 0.f, 0.f, 0.f};
 
   for (long long base = v0; base < v1; base += 64) {
     // ---- all loads of this step
@@ -165,7 +176,10 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     }
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-      if (4 * k >= n_here) break;                        // (uniform) no row left in this step
+      if (4 * k >= n_here) {                             // (uniform) no row left in this step
+        vreg[k] = w_u32x4{0u, 0u, 0u, 0u};               // meets weight 0 below: must be finite
+        continue;
+      }
       const int j = 4 * k + tg;
       const long long tj = token_of(base + (j < n_here ? j : n_here - 1));
       const __half* vrow = fp16_row(a.v, a, bh, tj);
@@ -216,11 +230,39 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     }
     __syncthreads();
 
-    // ---- scores: lane = token
+    // ---- scores: lane = token.  fp16 rows go through the matrix cores: 4x4x4 blocks, B = four
+    // consecutive channels of the lane's row (8 bytes as loaded), A = the same channels of the four
+    // heads (from wq), the four results land in the lane that holds the token.  Lanes whose row is
+    // a packed one take part with whatever their registers hold and are overwritten below.
     float s[NH];
+    {
+      w_float4_t sacc[NH4];
 #pragma unroll
-    for (int h = 0; h < NH; ++h) s[h] = 0.f;
+      for (int n = 0; n < NH4; ++n) sacc[n] = w_float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          w_u32x2 bw;
+          bw.x = hf ? kreg[i].z : kreg[i].x;
+          bw.y = hf ? kreg[i].w : kreg[i].y;
+          w_half4_t bop = __builtin_bit_cast(w_half4_t, bw);
+          if (KQ && k_packed) bop = w_half4_t{(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};   // finite operands only
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const w_half4_t aop = *reinterpret_cast<const w_half4_t*>(&wq[4 * n + (lane & 3)][8 * i + 4 * hf]);
+            sacc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, sacc[n], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+        s[4 * n] = sacc[n].x; s[4 * n + 1] = sacc[n].y; s[4 * n + 2] = sacc[n].z; s[4 * n + 3] = sacc[n].w;
+      }
+    }
     if (KQ && k_packed) {
+#pragma unroll
+      for (int h = 0; h < NH; ++h) s[h] = 0.f;
       // a packed row, group by group (Eq. hybrid_dequant): |S| * sum(q * field) + Zeff * sum(q),
       // the fields taken as they are stored
 #pragma unroll
@@ -271,22 +313,6 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
 #pragma unroll
         for (int h = 0; h < NH; ++h) s[h] += S * acc[h] + zeff * wqs[g][h];
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint32_t kw[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
-#pragma unroll
-        for (int h = 0; h < NH; ++h) {
-          const w_u32x4 qv = *reinterpret_cast<const w_u32x4*>(&wq[h][i * 8]);
-          const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const w_half2_t kk = __builtin_bit_cast(w_half2_t, kw[e]), qq = __builtin_bit_cast(w_half2_t, qw[e]);
-            s[h] += (float)kk[0] * (float)qq[0];
-            s[h] += (float)kk[1] * (float)qq[1];
-          }
-        }
-      }
     }
     __syncthreads();
     // ---- running softmax
@@ -295,17 +321,58 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
       const float sv = valid ? s[h] * c_log2 : -INFINITY;
       const float m_new = fmaxf(m_run[h], window_wave_max(sv));
       const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);
-      const float p = __builtin_amdgcn_exp2f(sv - m_new);
+      float p = __builtin_amdgcn_exp2f(sv - m_new);      // 0 for the idle lanes
+      if constexpr (!VQ) {
+        // the weight the matrix cores will use, so that the normaliser stays consistent
+        const _Float16 p16 = (_Float16)p;
+        p = (float)p16;
+        wp16[((lane & 3) * NH + h) * 16 + (lane >> 2)] = p16;
+      } else {
+        wp[lane][h] = p;
+      }
       l_run[h] = l_run[h] * alpha + window_wave_sum(p);
       m_run[h] = m_new;
+      if constexpr (VQ) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[h][e] *= alpha;
-      wp[lane][h] = p;                                   // 0 for the idle lanes
+        for (int e = 0; e < 8; ++e) o[h][e] *= alpha;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) oq[e][h / 4][h % 4] *= alpha;
+      }
     }
     __syncthreads();
     // ---- values: 16 lanes share one token row (8 channels = 16 bytes each), 4 rows per load
     // instruction; a lane keeps o[head][8 channels] of the tokens (4k + lane/16) and the four
     // lane groups are summed at the end.  Rows past the end carry probability 0.
+    if constexpr (!VQ) {
+      // matrix cores: contraction over four tokens (4 kq .. 4 kq + 3 of this lane group), B = one
+      // channel of this lane for those tokens (halves gathered from the four row registers),
+      // A = the fp16 weights of the four heads for the same tokens
+#pragma unroll
+      for (int kq = 0; kq < 4; ++kq) {
+        if (16 * kq >= n_here) break;                    // (uniform) no row left in this step
+        w_half4_t aop[NH4];
+#pragma unroll
+        for (int n = 0; n < NH4; ++n)
+          aop[n] = *reinterpret_cast<const w_half4_t*>(&wp16[(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          const uint32_t w0 = vreg[4 * kq][wd], w1 = vreg[4 * kq + 1][wd], w2 = vreg[4 * kq + 2][wd],
+                         w3 = vreg[4 * kq + 3][wd];
+          w_u32x2 lo, hi;
+          lo.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);   // low halves: channel 2 wd of tokens 0, 1
+          lo.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+          hi.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);   // high halves: channel 2 wd + 1
+          hi.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+          const w_half4_t blo = __builtin_bit_cast(w_half4_t, lo), bhi = __builtin_bit_cast(w_half4_t, hi);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            oq[2 * wd][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], blo, oq[2 * wd][n], 0, 0, 0);
+            oq[2 * wd + 1][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], bhi, oq[2 * wd + 1][n], 0, 0, 0);
+          }
+        }
+      }
+    } else {
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       if (4 * k >= n_here) break;                        // (uniform) no row left in this step
@@ -336,9 +403,16 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
           for (int e = 0; e < 8; ++e) o[n * 4 + i][e] += pv[i] * x[e];
       }
     }
+    }
     __syncthreads();
   }
 
+  if constexpr (!VQ) {
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[h][e] = oq[e][h / 4][h % 4];
+  }
   // ---- sum the four lane groups; lanes 0..15 then hold channels 8*lane .. 8*lane+7
 #pragma unroll
   for (int h = 0; h < NH; ++h)
