@@ -553,10 +553,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
-// Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it
-// (a 64-token chunk takes about 16 us of wall time against 1.8 us per tile, but little of it is
-// issue slots; the figure that balances the launch best, swept from 4 to 18, is about 13).
-inline int window_cost(long long len) { return (int)(2 + 11 * len / 64); }
+// Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it.  The
+// chunk runs at the lowest issue priority next to a partner that is busy about three quarters of
+// the time, so its wall time is several times its own instruction count; the slope is the one that
+// balances the launch best when swept (8 to 11 per 64 tokens: 11 on the 32k-token G = 32
+// configuration, 8 on the 8k x 32 G = 64 one, each 2 to 4 % better than the other's value).
+inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 8 : 11) * len / 64); }
 
 template <int KB, int VB, int G, bool ZK, bool ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
@@ -564,7 +566,7 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   // A window chunk costs its wavefront about as much time as window_cost() tiles: the wavefronts
   // that carry one get that many tiles fewer than the common quota.
   const int n_tiles = (n_both + TILE - 1) / TILE;
-  const int cost = win.n_chunks > 0 ? window_cost((win.na + win.nb + win.n_chunks - 1) / win.n_chunks) : 0;
+  const int cost = win.n_chunks > 0 ? window_cost((win.na + win.nb + win.n_chunks - 1) / win.n_chunks, G) : 0;
   const int quota = (n_tiles + win.n_chunks * cost + n_splits - 1) / n_splits;
   int win_tiles = quota > cost ? quota - cost : 0;
   if (win.n_chunks > 0 && win_tiles > n_tiles / win.n_chunks) win_tiles = n_tiles / win.n_chunks;

@@ -47,15 +47,32 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
   return asym ? S * (float)field + __half2float(tv.zeros[si]) : S * (float)((int)field - (1 << (bits - 1)));
 }
 
-// fp16 row of token t if that tensor keeps it in fp16 (sink window, recent ring, fp16 store), else null.
+// fp16 row of token t if that tensor keeps it in fp16 (sink window, recent ring, fp16 store, or the
+// not yet appended newest token), else null.  Written for a caller that asks for many rows per
+// lane: everything that depends on bh alone is wave-uniform (scalar registers), the per-lane part
+// is 32-bit (token indices stay below 2^24: capacity * head_dim <= 2^31), and the ring slot
+// t mod slots comes from a float reciprocal with a one-step correction instead of an integer
+// division (a 64-bit modulo per row used to cost more instructions than the row's arithmetic).
 __device__ __forceinline__ const __half* fp16_row(const TensorView& tv, const AttnArgs& a, long long bh, long long t) {
   constexpr int D = kHeadDim;
-  if (tv.newest && t == a.n_tokens - 1) return tv.newest + bh * D;
-  if (t < tv.n_sink) return tv.sink + (bh * a.w_sink + t) * D;
-  const long long row = t - a.w_sink;
-  if (row >= tv.n_quant) return tv.ring + (bh * tv.slots + (t % tv.slots)) * D;
-  if (tv.form == kFp16) return reinterpret_cast<const __half*>(tv.codes) + (bh * a.capacity + row) * D;
-  return nullptr;
+  const uint32_t tt = (uint32_t)t, ws = (uint32_t)a.w_sink, slots = (uint32_t)tv.slots;
+  const uint32_t row = tt - ws;                               // meaningful when tt >= n_sink
+  // tt mod slots
+  uint32_t q = (uint32_t)((float)tt * (1.0f / (float)slots));
+  uint32_t slot = tt - q * slots;                             // off by at most one multiple of slots
+  slot = (int32_t)slot < 0 ? slot + slots : slot;
+  slot = slot >= slots ? slot - slots : slot;
+  const bool is_new = tv.newest != nullptr && tt == (uint32_t)(a.n_tokens - 1);
+  const bool is_sink = tt < (uint32_t)tv.n_sink;
+  const bool is_ring = !is_sink && row >= (uint32_t)tv.n_quant;
+  const bool is_store = tv.form == kFp16;
+  const __half* base_new = tv.newest + bh * D;
+  const __half* base_sink = tv.sink + bh * a.w_sink * D;
+  const __half* base_ring = tv.ring + bh * tv.slots * D;
+  const __half* base_store = reinterpret_cast<const __half*>(tv.codes) + bh * a.capacity * D;
+  const __half* base = is_new ? base_new : is_sink ? base_sink : is_ring ? base_ring : base_store;
+  const uint32_t off = is_new ? 0u : is_sink ? tt * D : is_ring ? slot * D : row * D;
+  return (is_new || is_sink || is_ring || is_store) ? base + off : nullptr;
 }
 
 // Wave-wide reductions: butterflies inside a row of 16 lanes via DPP, then the four rows through
@@ -124,7 +141,12 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   __shared__ __attribute__((aligned(16))) _Float16 wp16[VQ ? 1 : 4 * NH * 16];
 
   const int cg = lane & 15, tg = lane >> 4;
-  auto token_of = [&](long long v) -> long long { return v < na ? v : b0 + (v - na); };
+  // (every index here is below 2^24: 32-bit arithmetic per lane)
+  const uint32_t na32 = (uint32_t)na, b032 = (uint32_t)b0;
+  auto token_of = [&](long long v) -> long long {
+    const uint32_t vv = (uint32_t)v;
+    return (long long)(vv < na32 ? vv : b032 + (vv - na32));
+  };
 
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;    // log2(e) / sqrt(d)
   // o[h][e]: head h, channel 8 cg + e, the tokens 4 k + tg of every step.  Without packed value
@@ -169,7 +191,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
 #pragma unroll
           for (int i = 0; i < NG / 2; ++i) kz[i] = zp[i];
         }
-      } else if (krow) {
+      } else {                                              // an fp16 row (always, unless KQ)
 #pragma unroll
         for (int i = 0; i < 16; ++i) kreg[i] = *reinterpret_cast<const w_u32x4*>(krow + i * 8);
       }
@@ -195,7 +217,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         m.y = (uint32_t)__half_as_ushort(a.v.scales[si]);
         if (a.v.zeros) m.z = (uint32_t)__half_as_ushort(a.v.zeros[si]);
         vreg[k] = m;
-      } else if (vrow) {
+      } else {                                              // an fp16 row (always, unless VQ)
         vreg[k] = *reinterpret_cast<const w_u32x4*>(vrow + 8 * cg);
       }
     }
