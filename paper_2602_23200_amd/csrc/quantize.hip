@@ -221,13 +221,19 @@ __device__ inline uint32_t quantize_group_lanes(const float (&x)[G / 8], int sub
   return w;
 }
 
+// Index arithmetic of one launch is 32-bit: the host refuses launches of 2^32 or more threads, token
+// indices stay below 2^24 (capacity * head_dim <= 2^31), and a 64-bit division by a run-time value
+// is an inlined routine of well over a hundred instructions where the 32-bit one takes about twenty.
+__device__ __forceinline__ uint32_t div32(long long n, long long d) { return (uint32_t)n / (uint32_t)d; }
+__device__ __forceinline__ uint32_t mod32(long long n, long long d) { return (uint32_t)n % (uint32_t)d; }
+
 // Where the fp16 row of token t (absolute index) of sequence-head bh lives when the quantiser
 // wants it: still in the recent ring if it was appended by an earlier call, else in x_new.
 __device__ __forceinline__ const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
                                           long long t, bool& from_new) {
   from_new = t >= a.n_old;
   if (from_new) return j.x_new + ((bh * a.t_new) + (t - a.n_old)) * kHeadDim;
-  return j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
+  return j.ring + (bh * j.slots + mod32(t, j.slots)) * kHeadDim;
 }
 
 // Which of the t_new new tokens (index i, absolute token n_old + i) go to a window: i < n_a to
@@ -251,17 +257,17 @@ __device__ __forceinline__ void window_copy(const QuantArgs& a, const QuantTenso
   const long long n_cp = sp.n_a + (a.t_new - sp.i_b);
   if (idx >= BH * n_cp * CPR) return;
   const int ch = (int)(idx % CPR);
-  const long long k = (idx / CPR) % n_cp;
-  const long long bh = idx / (CPR * n_cp);
+  const long long bh = div32(idx / CPR, n_cp);
+  const long long k = idx / CPR - bh * n_cp;
   const long long i = k < sp.n_a ? k : sp.i_b + (k - sp.n_a);
   const long long t = a.n_old + i;
   __half* dst;
   if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
-  else dst = j.ring + (bh * j.slots + (t % j.slots)) * kHeadDim;
+  else dst = j.ring + (bh * j.slots + mod32(t, j.slots)) * kHeadDim;
   uint4 raw = *reinterpret_cast<const uint4*>(j.x_new + (bh * a.t_new + i) * kHeadDim + ch * 8);
   if (j.normalise) {
     __half* h = reinterpret_cast<__half*>(&raw);
-    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
+    const float* inv = a.inv_norm + mod32(bh, a.n_kv_heads) * kHeadDim + ch * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) h[e] = scaled_half(h2f(h[e]), inv[e]);
   }
@@ -313,12 +319,12 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     constexpr int GPR = kHeadDim / G;                    // groups per row
     if (idx >= BH * n_rows * GPR) return;
     const int g = (int)(idx % GPR);
-    const long long row = j.row_begin + (idx / GPR) % n_rows;
-    const long long bh = idx / (GPR * n_rows);
+    const long long bh = div32(idx / GPR, n_rows);
+    const long long row = j.row_begin + (idx / GPR - bh * n_rows);
     bool from_new;
     const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G;
     const bool norm = from_new && j.normalise;
-    const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G;
+    const float* inv = a.inv_norm + mod32(bh, a.n_kv_heads) * kHeadDim + g * G;
     uint32_t words[W];
     __half s, z;
     if constexpr (G <= 32) {
@@ -376,8 +382,8 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     const int sub = (int)(idx % 8);
     const long long gi = idx / 8;
     const int g = (int)(gi % GPR);
-    const long long row = j.row_begin + (gi / GPR) % n_rows;
-    const long long bh = gi / (GPR * n_rows);
+    const long long bh = div32(gi / GPR, n_rows);
+    const long long row = j.row_begin + (gi / GPR - bh * n_rows);
     bool from_new;
     const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G + sub * E;
     float x[E];
@@ -393,7 +399,7 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
       for (int e = 0; e < 8; ++e) x[e] = h2f(h[e]);
     }
     if (from_new && j.normalise) {
-      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + g * G + sub * E;
+      const float* inv = a.inv_norm + mod32(bh, a.n_kv_heads) * kHeadDim + g * G + sub * E;
 #pragma unroll
       for (int i = 0; i < E; ++i) x[i] = h2f(scaled_half(x[i], inv[i]));
     }
@@ -416,9 +422,9 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     const long long n_groups = n_rows / G;
     if (idx >= BH * n_groups * kHeadDim) return;
     const int c = (int)(idx % kHeadDim);
-    const long long tg = j.row_begin / G + (idx / kHeadDim) % n_groups;   // token-group index in the store
-    const long long bh = idx / (kHeadDim * n_groups);
-    const float inv = j.normalise ? a.inv_norm[(bh % a.n_kv_heads) * kHeadDim + c] : 1.f;
+    const long long bh = div32(idx / kHeadDim, n_groups);
+    const long long tg = j.row_begin / G + (idx / kHeadDim - bh * n_groups);   // token-group index in the store
+    const float inv = j.normalise ? a.inv_norm[mod32(bh, a.n_kv_heads) * kHeadDim + c] : 1.f;
     uint32_t words[W];
     __half s, z;
     auto run = [&](auto fetch) {
@@ -467,14 +473,14 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     constexpr int CPR = kHeadDim / 8;
     if (idx >= BH * n_rows * CPR) return;
     const int ch = (int)(idx % CPR);
-    const long long row = j.row_begin + (idx / CPR) % n_rows;
-    const long long bh = idx / (CPR * n_rows);
+    const long long bh = div32(idx / CPR, n_rows);
+    const long long row = j.row_begin + (idx / CPR - bh * n_rows);
     bool from_new;
     const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + ch * 8;
     uint4 raw = *reinterpret_cast<const uint4*>(src);
     if (from_new && j.normalise) {
       __half* h = reinterpret_cast<__half*>(&raw);
-      const float* inv = a.inv_norm + (bh % a.n_kv_heads) * kHeadDim + ch * 8;
+      const float* inv = a.inv_norm + mod32(bh, a.n_kv_heads) * kHeadDim + ch * 8;
 #pragma unroll
       for (int e = 0; e < 8; ++e) h[e] = scaled_half(h2f(h[e]), inv[e]);
     }
@@ -536,6 +542,7 @@ hipError_t launch_quantize_t(const QuantArgs& a, hipStream_t stream, const AttnA
     else n = BH * rows * (kHeadDim / 8);
     threads = n > threads ? n : threads;
   }
+  if (threads >= (1LL << 32)) return hipErrorInvalidValue;   // (device index arithmetic is 32-bit)
   long long cthreads = 0;
   for (int w = 0; w < 2; ++w) {
     const CopySpan sp = copy_span(a, a.job[w]);
