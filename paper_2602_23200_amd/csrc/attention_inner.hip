@@ -134,7 +134,8 @@ struct TileRegs {
 
 // KB, VB: widths of the key and value codes.
 template <int KB, int VB, int G, int NH4, bool ZK, bool ZV>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles) {
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles, int base_t, int rem_t,
+                                                                                                 int r) {
   constexpr int LBK = KB == 3 ? 2 : KB, LBV = VB == 3 ? 2 : VB;   // field width of the (low) plane
   constexpr bool HIK = KB == 3, HIV = VB == 3;                     // a plane of high bits follows it
   using FK = Fields<LBK>;
@@ -149,10 +150,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int HALFK = 1 << (KB - 1), HALFV = 1 << (VB - 1);
   constexpr int NH = NH4 * 4;
 
+  // No division on the way to the first load: the grid is (splits, kv heads, batch), and the
+  // host passes the quotients (heads per kv head; tiles per plain wavefront and their remainder).
   const int lane = threadIdx.x;
-  const long long bh = blockIdx.y;
-  const int b = (int)(bh / a.n_kv_heads), hk = (int)(bh % a.n_kv_heads);
-  const int r = a.n_q_heads / a.n_kv_heads;
+  const int hk = (int)blockIdx.y, b = (int)blockIdx.z;
+  const long long bh = (long long)b * a.n_kv_heads + hk;
   constexpr bool has_kz = ZK, has_vz = ZV;       // zero-point arrays exist unless the tensor is symmetric-only
 
   // ---- tile range of this wavefront.  The first win.n_chunks wavefronts of a (batch, kv-head)
@@ -165,8 +167,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     t0 = s_idx * win_tiles;
     t1 = t0 + win_tiles;
   } else {
-    const int rest = n_tiles - win.n_chunks * win_tiles, others = n_splits - win.n_chunks, j = s_idx - win.n_chunks;
-    const int base_t = rest / others, rem_t = rest % others;
+    const int j = s_idx - win.n_chunks;                  // base_t, rem_t: (n_tiles - n_chunks * win_tiles) divided by the plain wavefronts
     t0 = win.n_chunks * win_tiles + j * base_t + (j < rem_t ? j : rem_t);
     t1 = t0 + base_t + (j < rem_t ? 1 : 0);
   }
@@ -571,13 +572,16 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   int win_tiles = quota > cost ? quota - cost : 0;
   if (win.n_chunks > 0 && win_tiles > n_tiles / win.n_chunks) win_tiles = n_tiles / win.n_chunks;
   if (n_splits <= win.n_chunks) return hipErrorInvalidValue;      // the host gives at least one plain wavefront
-  dim3 grid((unsigned)n_splits, (unsigned)(a.batch * a.n_kv_heads));
+  if (a.batch > 65535 || a.n_kv_heads > 65535) return hipErrorInvalidValue;
+  const int rest = n_tiles - win.n_chunks * win_tiles, others = n_splits - win.n_chunks;
+  const int base_t = rest / others, rem_t = rest % others;
+  dim3 grid((unsigned)n_splits, (unsigned)a.n_kv_heads, (unsigned)a.batch);
   if (r <= 4)
     hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
-                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
+                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
   else
     hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
-                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles);
+                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
   return hipGetLastError();
 }
 

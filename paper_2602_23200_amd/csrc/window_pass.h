@@ -126,10 +126,11 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   constexpr uint32_t FMASK = (1u << BITS) - 1u;
   constexpr float HALFCODE = (float)(1 << (BITS - 1));
   const int lane = threadIdx.x & 63;
-  const int b = (int)(bh / a.n_kv_heads), hk = (int)(bh % a.n_kv_heads);
+  // (32-bit: bh is a grid index)
+  const int b = (int)((uint32_t)bh / (uint32_t)a.n_kv_heads), hk = (int)((uint32_t)bh % (uint32_t)a.n_kv_heads);
   const int r = a.n_q_heads / a.n_kv_heads;
   const long long total = na + nb;
-  const long long chunk_len = (total + n_chunks - 1) / n_chunks;
+  const long long chunk_len = (long long)((uint32_t)(total + n_chunks - 1) / (uint32_t)n_chunks);
   const long long v0 = chunk * chunk_len;
   const long long v1 = v0 + chunk_len < total ? v0 + chunk_len : total;
 
