@@ -282,6 +282,25 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
   __syncthreads();
 
+  // ---- A operands of the zero-point term: sum over groups of Zeff_g * (sum of q over group g) is a
+  // 4 (heads) x 4 (groups) product per token, one more matrix instruction.  The group sums of q
+  // enter as two fp16 pieces (hi + lo, 2^-22 relative) so that the term keeps fp32 accuracy; Zeff
+  // is an exact fp16 number (Z for an asymmetric group, -2^(b-1) S for a symmetric one).  The
+  // operands carry 2 * qsum and Zeff / 2: S is at most 65504 / (2^(b-1) - 1), so 2^(b-2) S is
+  // finite in fp16 for every finite cache where 2^(b-1) S is not; Z / 2 is exact unless Z is an fp16
+  // denormal with an odd last bit (2^-25 off).
+  half4_t qs_hi[NH4], qs_lo[NH4];
+#pragma unroll
+  for (int n = 0; n < NH4; ++n) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float v = g < NG ? 2.f * qsum[n][g][lane & 3] : 0.f;
+      const _Float16 hi = (_Float16)v;
+      qs_hi[n][g] = hi;
+      qs_lo[n][g] = (_Float16)(v - (float)hi);
+    }
+  }
+
   // ---- running softmax state (log2 domain) and output accumulators.
   // m_run is a reference level, not the exact running maximum: it is raised (and l, o rescaled)
   // only when some score exceeds it by more than kSlack, so the common tile pays no wave-wide
@@ -367,30 +386,37 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // Zeff = Z - 2^(b-1) * max(s, 0) needs no select (Z is stored as +0 for symmetric groups).
     // Scales and zero-points enter the FMAs as fp16 sources; the constant factor is applied once.
     float e[NH], t[NH];
+    {
+      // Zeff / 2 of this token's groups as fp16: Z / 2 - 2^(b-2) max(s, 0) (one of the two terms is 0)
+      u32x2 zw = {0u, 0u};
 #pragma unroll
-    for (int h = 0; h < NH; ++h) { e[h] = p_shift - m_run[h]; t[h] = 0.f; }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const uint32_t spair = cur.ks[g / 2];
-      const _Float16 s16 = half_of(spair, g & 1);
-      float zeff;
-      if constexpr (has_kz) {
-        const uint32_t mpair = __builtin_bit_cast(
-            uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
-        zeff = __builtin_fmaf((float)half_of(mpair, g & 1), (float)(-HALFK), (float)half_of(cur.kz[g / 2], g & 1));
-      } else {
-        zeff = (float)s16 * (float)(-HALFK);
+      for (int gp = 0; gp < NG / 2; ++gp) {
+        const half2_t sp = __builtin_bit_cast(half2_t, cur.ks[gp]);
+        const half2_t mp = __builtin_elementwise_max(sp, half2_t{(_Float16)0, (_Float16)0});
+        half2_t zp;
+        constexpr _Float16 kNegQuarterK = (_Float16)(-HALFK / 2), kHalf = (_Float16)0.5f;
+        if constexpr (has_kz)
+          zp = mp * half2_t{kNegQuarterK, kNegQuarterK} + __builtin_bit_cast(half2_t, cur.kz[gp]) * half2_t{kHalf, kHalf};
+        else zp = sp * half2_t{kNegQuarterK, kNegQuarterK};
+        zw[gp] = __builtin_bit_cast(uint32_t, zp);
       }
-      const float S = __builtin_fabsf((float)s16);
+      const half4_t zop = __builtin_bit_cast(half4_t, zw);
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
-        const float4_t qs = *reinterpret_cast<const float4_t*>(&qsum[n][g][0]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          t[n * 4 + i] = __builtin_fmaf(S, acc[g][n][i], t[n * 4 + i]);
-          e[n * 4 + i] = __builtin_fmaf(zeff, qs[i], e[n * 4 + i]);
-        }
+        float4_t ez = float4_t{p_shift - m_run[4 * n], p_shift - m_run[4 * n + 1], p_shift - m_run[4 * n + 2],
+                               p_shift - m_run[4 * n + 3]};
+        ez = __builtin_amdgcn_mfma_f32_4x4x4f16(qs_hi[n], zop, ez, 0, 0, 0);
+        ez = __builtin_amdgcn_mfma_f32_4x4x4f16(qs_lo[n], zop, ez, 0, 0, 0);
+        e[4 * n] = ez.x; e[4 * n + 1] = ez.y; e[4 * n + 2] = ez.z; e[4 * n + 3] = ez.w;
       }
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) t[h] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float S = __builtin_fabsf((float)half_of(cur.ks[g / 2], g & 1));
+#pragma unroll
+      for (int h = 0; h < NH; ++h) t[h] = __builtin_fmaf(S, acc[g][h / 4][h % 4], t[h]);
     }
 #pragma unroll
     for (int h = 0; h < NH; ++h)

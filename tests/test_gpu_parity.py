@@ -143,6 +143,29 @@ def test_attention_small_all_variants(env, kind, bits, group, mode):
     assert max_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("bits,mode", [(2, orc.SYM), (2, orc.HYBRID), (3, orc.HYBRID), (4, orc.SYM), (4, orc.HYBRID)])
+def test_attention_keys_near_the_top_of_fp16(env, bits, mode):
+    """Forty tokens spread over sink, quantised region and recent window carry keys up to 6e4 in
+    magnitude, so that 2^(b-1) times the scale of a symmetric group lies beyond fp16: the
+    zero-point term of the scores has to stay finite, and the softmax has to follow scores
+    thousands of units apart."""
+    torch, iq = env
+    w = small(bits=bits, k_mode=mode, v_mode=mode, n_tokens=900)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    K = K.astype(np.float32)
+    big = np.random.default_rng(5).choice(w.n_tokens, 40, replace=False)
+    big[:3] = [1, 400, w.n_tokens - 2]
+    K[:, :, big] *= 8192.0
+    K = np.clip(K, -6.0e4, 6.0e4).astype(np.float16)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    assert np.isfinite(want).all()
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert np.isfinite(got).all()
+    assert max_rel_err(got, want) <= TOL
+
+
 @pytest.mark.parametrize("n_tokens", [1, 2, 4, 5, 51, 52, 53, 83, 84, 85, 116, 117, 180])
 @pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
 def test_attention_edge_lengths(env, kind, n_tokens):
