@@ -187,9 +187,12 @@ int innerq_quantize_append(const innerq_config_t *cfg, innerq_cache_t *cache, co
  *              contents need not be initialised and are undefined afterwards
  * Accumulation is fp32.  n_tokens must be >= 1.
  * Input range: inputs are assumed finite (NaN / Inf behaviour is unspecified).  On the fused
- * kernels the query (after q_scale) enters the matrix cores as fp16 times a power of two:
- * |q| must stay below 4094 for 2- and 4-bit keys and below 1023 for 3-bit keys; larger
- * values overflow to infinity.  Nothing checks this (the query is device data). */
+ * kernels the query (after q_scale) enters the matrix cores as fp16 times a power of two.  The
+ * inner-grouped kernel chooses that power per head from the head's largest |q|, so every finite
+ * fp16 query is accepted and the accuracy does not depend on its magnitude.  The outer-grouped
+ * comparison kernel uses fixed powers: there |q| must stay below 4094 for 2- and 4-bit keys and
+ * below 1023 for 3-bit keys (larger values overflow to infinity; nothing checks this, the query
+ * is device data), and queries far below 1 in magnitude lose precision. */
 int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *cache,
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -246,6 +246,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   Regs bufA, bufB;
   if (t1 > t0) load_tile(t0, bufA);
 
+  float q_coef[NH];
   // ---- query: fp16 (optionally rescaled), position factors folded in.  A lane takes 8
   // consecutive channels of one head (one 16-byte load); the channels of one key group sit in
   // G/8 neighbouring lanes, so the group sums of q come from a few DPP adds.
@@ -254,23 +255,43 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int idx = rnd * 64 + lane;
     const int h = idx / (D / 8), c0 = 8 * (idx % (D / 8));
     const uint32_t rw[4] = {q_raw[rnd].x, q_raw[rnd].y, q_raw[rnd].z, q_raw[rnd].w};
-    float part = 0.f;
+    float qv[8], part = 0.f, mx = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (e & 1) ? (rw[e / 2] >> 16) : (rw[e / 2] & 0xffffu);
-      float qv = __half2float(__ushort_as_half((unsigned short)hb));
-      if (a.q_scale) qv = __half2float(scaled_half(qv, a.q_scale[hk * D + c0 + e]));
-      part += qv;
+      qv[e] = __half2float(__ushort_as_half((unsigned short)hb));
+      if (a.q_scale) qv[e] = __half2float(scaled_half(qv[e], a.q_scale[hk * D + c0 + e]));
+      part += qv[e];
+      mx = __builtin_fmaxf(mx, __builtin_fabsf(qv[e]));
+    }
+    // power of two that brings the head's largest |q| into [2^8, 2^9): the position factors span
+    // up to 2^-10 .. 2^6, so the table entries stay normal fp16 numbers down to 2^-13 of the
+    // head's maximum whatever the magnitude of the queries (a head is D/8 = 16 neighbouring lanes)
+    static_assert(D / 8 == 16, "a head is one 16-lane row of the cross-lane operations below");
+    mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, mx), 0xB1, 0xF, 0xF, true)));    // lane ^ 1
+    mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, mx), 0x4E, 0xF, 0xF, true)));    // lane ^ 2
+    mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, mx), 0x141, 0xF, 0xF, true)));   // mirror within 8
+    mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, mx), 0x140, 0xF, 0xF, true)));   // mirror within 16
+    const int q_exp = mx > 0.f ? (int)((__float_as_uint(mx) >> 23) & 0xffu) - 127 : 8;
+    const float q_pow = __uint_as_float((uint32_t)(127 + 8 - q_exp) << 23);
+    // per-head constant of the score, log2e/sqrt(d) * 2^20 / (the head's factor): wave-uniform, so it
+    // goes to scalar registers straight from the first lane of each head's row
+    const float coef = (kSmScale * kLog2e * 1048576.0f) * __uint_as_float((uint32_t)(127 - 8 + q_exp) << 23);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      q_coef[rnd * 4 + j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, coef), 16 * j));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
       const int c = c0 + e;
       const int word = c / FK::FPW, ep = c % FK::FPW;
       const int f = ep % FK::HALF;
       const float factor = (float)(1 << (4 + LBK * 4)) / (float)(1 << (LBK * FK::pos(f) + LBK * 4));   // 2^(4 - b*pos)
-      qA[(h * NW + word) * (MPWK * 4) + FK::slot(ep)] = (_Float16)(qv * factor);
+      qA[(h * NW + word) * (MPWK * 4) + FK::slot(ep)] = (_Float16)(qv[e] * q_pow * factor);
       if constexpr (HIK) {
         // 1-bit field at position pos of its half: 2^(pos - 24); weight 4 -> q * 2^(6 - pos)
         const int word1 = c / 32, ep1 = c % 32;
         const float factor1 = 64.0f / (float)(1 << F1::pos(ep1 % 16));
-        qA1[(h * (D / 32) + word1) * (F1::MPW * 4) + F1::slot(ep1)] = (_Float16)(qv * factor1);
+        qA1[(h * (D / 32) + word1) * (F1::MPW * 4) + F1::slot(ep1)] = (_Float16)(qv[e] * q_pow * factor1);
       }
     }
     // sum over the G/8 lanes of the group (4 lanes: one quad; 8 lanes: two quads)
@@ -420,7 +441,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
 #pragma unroll
     for (int h = 0; h < NH; ++h)
-      e[h] = __builtin_fmaf(kSmScale * kLog2e * 1048576.0f, t[h], e[h]);   // 2^20 undoes the operand factors
+      e[h] = __builtin_fmaf(q_coef[h], t[h], e[h]);   // undoes the operand factors (2^20) and the head's query factor
 
     // ================= running softmax (Eq. att:2), probabilities to the operand table =================
     if (tile * TILE + (TILE - 1) > last_row) {         // ragged last tile: lanes past the end weigh nothing

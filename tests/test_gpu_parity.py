@@ -166,6 +166,23 @@ def test_attention_keys_near_the_top_of_fp16(env, bits, mode):
     assert max_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("log2_q", [-13, -6, 6])
+@pytest.mark.parametrize("bits,mode", [(2, orc.SYM), (2, orc.HYBRID), (3, orc.HYBRID), (4, orc.HYBRID)])
+def test_attention_query_magnitudes(env, bits, mode, log2_q):
+    """Queries scaled by 2^-13 (mostly fp16 denormals), 2^-6 and 2^6, keys scaled the other way so
+    that the scores keep their size: the fused kernel's query table carries a power of two per
+    head, so its accuracy must not depend on the magnitude of q."""
+    torch, iq = env
+    w = small(bits=bits, k_mode=mode, v_mode=mode, n_tokens=900)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    K = np.clip(K.astype(np.float32) * 2.0 ** (-log2_q - 1), -6.0e4, 6.0e4).astype(np.float16)
+    q = (wl.query(w).astype(np.float32) * 2.0 ** log2_q).astype(np.float16)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert max_rel_err(got, want) <= TOL
+
+
 @pytest.mark.parametrize("n_tokens", [1, 2, 4, 5, 51, 52, 53, 83, 84, 85, 116, 117, 180])
 @pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
 def test_attention_edge_lengths(env, kind, n_tokens):
