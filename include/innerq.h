@@ -190,9 +190,8 @@ int innerq_quantize_append(const innerq_config_t *cfg, innerq_cache_t *cache, co
  * kernels the query (after q_scale) enters the matrix cores as fp16 times a power of two.  The
  * inner-grouped kernel chooses that power per head from the head's largest |q|, so every finite
  * fp16 query is accepted and the accuracy does not depend on its magnitude.  The outer-grouped
- * comparison kernel uses fixed powers: there |q| must stay below 4094 for 2- and 4-bit keys and
- * below 1023 for 3-bit keys (larger values overflow to infinity; nothing checks this, the query
- * is device data), and queries far below 1 in magnitude lose precision. */
+ * comparison kernel multiplies the fp16 query as it is with keys dequantised to fp16: there the
+ * dequantised keys must stay within the fp16 range (nothing checks this: device data). */
 int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *cache,
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
