@@ -196,6 +196,25 @@ int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *ca
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* innerq_decode_attention for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, launch plan and results as innerq_decode_attention, except that the
+ * split-K partials live in an array that is part of the library's code object
+ * (INNERQ_STATIC_WORKSPACE_BYTES bytes of device memory per GPU, held from the first use of the
+ * library on that GPU until the process ends).  The call allocates and frees nothing; on its
+ * first use on a device it looks the array's device address up (a symbol query, no allocation:
+ * make that first call outside a graph capture).
+ *   - INNERQ_E_WORKSPACE if innerq_workspace_bytes(cfg) exceeds INNERQ_STATIC_WORKSPACE_BYTES
+ *     (nothing is launched); INNERQ_E_HIP if the address lookup fails.
+ *   - The partials need no clearing: every slot a call reads was written by that call.
+ *   - All calls on one GPU share the one array: two calls that overlap in time on the same GPU
+ *     (different streams or host threads) race on it and give undefined outputs.  Calls on one
+ *     stream are ordered and safe. */
+#define INNERQ_STATIC_WORKSPACE_BYTES (32u << 20)
+int innerq_decode_attention_static(const innerq_config_t *cfg, const innerq_cache_t *cache,
+                                   const void *q_fp16, const float *q_scale, void *out,
+                                   int out_is_fp32, void *hip_stream);
+
 /* Quantisation off the critical path of a decode step (the paper names this as future work at
  * the end of its Section "Latency": the quantisation of evicted tokens can be overlapped with
  * attention).  What leaves the recent windows at step t + 1 is already known at step t, and

@@ -73,6 +73,9 @@ def lib() -> C.CDLL:
         L.innerq_decode_attention.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.innerq_decode_attention.restype = C.c_int
+        L.innerq_decode_attention_static.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                     C.c_void_p]
+        L.innerq_decode_attention_static.restype = C.c_int
         L.innerq_quantize_ahead.argtypes = [cfgp, cachep, C.c_void_p]
         L.innerq_quantize_ahead.restype = C.c_int
         L.innerq_decode_attention_next.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -206,6 +209,23 @@ def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, 
                                        workspace.numel() * workspace.element_size(), _stream(stream))
     if st != OK:
         raise InnerQError(st, "innerq_decode_attention")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def innerq_decode_attention_static(cache: Cache, q, out=None, q_scale=None, stream=None):
+    """innerq_decode_attention with the split-K partials in the library's own static device array (no workspace)."""
+    import torch
+    assert q.dtype == torch.float16 and q.is_contiguous() and q.is_cuda
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    assert out.is_contiguous() and out.dtype in (torch.float32, torch.float16)
+    st = lib().innerq_decode_attention_static(C.byref(cache.cfg), C.byref(cache.c), q.data_ptr(), _ptr(q_scale),
+                                              out.data_ptr(), int(out.dtype == torch.float32), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_decode_attention_static")
     return out
 
 

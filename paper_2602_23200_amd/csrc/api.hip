@@ -1,6 +1,8 @@
 // C ABI of libinnerq (see include/innerq.h): argument checks, the window /
 // eviction arithmetic on the host, and kernel dispatch.  No device memory is
 // allocated here and nothing synchronises.
+#include <mutex>
+
 #include "innerq_dev.h"
 
 using namespace innerq;
@@ -401,6 +403,46 @@ int innerq_decode_attention(const innerq_config_t* cfg, const innerq_cache_t* ca
   if (st != INNERQ_OK) return st;
   return attention_impl(cfg, cache, cache->n_tokens, nullptr, nullptr, q_fp16, q_scale, out, out_is_fp32, workspace,
                         workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+// Split-K partials for innerq_decode_attention_static: one array per GPU, part of the loaded code
+// object, so no allocation call is ever made for it.  Host code never uses the array's name as an
+// address; it asks the runtime for the device address once per device and passes that.
+static __device__ __align__(256) unsigned char scratch[INNERQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64] = {nullptr};        // per device, filled on the first call with that device current
+
+// Device address of `scratch` on the current device (null on failure).
+void* static_workspace() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int innerq_decode_attention_static(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* q_fp16,
+                                   const float* q_scale, void* out, int out_is_fp32, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (innerq_workspace_bytes(cfg) > (size_t)INNERQ_STATIC_WORKSPACE_BYTES) return INNERQ_E_WORKSPACE;
+  void* ws = static_workspace();
+  if (!ws) return INNERQ_E_HIP;
+  return attention_impl(cfg, cache, cache->n_tokens, nullptr, nullptr, q_fp16, q_scale, out, out_is_fp32, ws,
+                        (size_t)INNERQ_STATIC_WORKSPACE_BYTES, hip_stream);
 }
 
 int innerq_decode_attention_next(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* k_new,

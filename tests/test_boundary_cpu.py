@@ -134,3 +134,18 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert L.innerq_calibrate_key_norm(C.byref(c), 4096, 0, 0, 4096, 4096, None) == iq.E_ARG
     bad, _ = cfg_of(w, bits=5)
     assert L.innerq_quantize_append(C.byref(bad), C.byref(cache), 4096, 4096, 1, None, None) == iq.E_UNSUPPORTED
+
+
+def test_static_workspace_entry_rejects_what_does_not_fit():
+    """The size check comes before any device call, so it can be exercised without a GPU."""
+    L = iq.lib()
+    # 512 sequences x 32 query heads need more partial slots than the static array holds
+    cfg = iq.make_config(512, 32, 8, 128, 2, 32, 4, 128, capacity_tokens=256)
+    assert iq.innerq_workspace_bytes(cfg) > iq.STATIC_WORKSPACE_BYTES
+    cache = iq.innerq_cache_t()
+    for n in iq.BUFFER_NAMES:
+        setattr(cache, n, 4096)
+    cache.n_tokens = 8
+    assert L.innerq_decode_attention_static(C.byref(cfg), C.byref(cache), 4096, None, 4096, 1, None) == iq.E_WORKSPACE
+    header = open(os.path.join(ROOT, "include", "innerq.h")).read()
+    assert f"INNERQ_STATIC_WORKSPACE_BYTES ({iq.STATIC_WORKSPACE_BYTES >> 20}u << 20)" in header
