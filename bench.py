@@ -53,6 +53,11 @@ def parse():
                    help="0: the default fused kernel (4x4x4 fp16 matrix instructions); 1: the fp8 x fp4 "
                         "block-scaled kernel for 2-bit caches (comparison runs)")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--min-timed-ms", type=float, default=50.0,
+                   help="the pass of --steps steps is repeated until the timed region is at least this long "
+                        "(reported as `repeats`; 0: exactly one pass)")
+    p.add_argument("--no-comparison", action="store_true",
+                   help="skip the fp16 and outer-grouped comparison kernels on the same data")
     p.add_argument("--asym-frac", type=float, default=None, metavar="F",
                    help="fill the caches with crafted groups of which a fraction F is quantised asymmetrically "
                         "in hybrid mode (the rest symmetrically): the density sweep of the flag matrix "
@@ -67,6 +72,7 @@ def parse():
 
 
 PREWARM_MAX_STEPS = 1024     # cap of the device pre-warm (sizes the caches)
+TIMED_MAX_STEPS = 4096       # cap of the repeated timed passes beyond the first (sizes the caches)
 
 
 class Hip:
@@ -165,6 +171,59 @@ def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None):
     return cache
 
 
+KERNEL_SOURCES = {"inner": ["attention_inner.hip", "window_pass.h", "innerq_dev.h"],
+                  "outer": ["attention_outer.hip", "window_pass.h", "innerq_dev.h"],
+                  "fp16": ["attention_fp16.hip", "window_pass.h", "innerq_dev.h"]}
+
+
+def kernel_sources_sha256(kind):
+    """Hash of the source files of one fused attention kernel (ties a recorded profile to a build)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES[kind]:
+        h.update(open(os.path.join(ROOT, "paper_2602_23200_amd", "csrc", name), "rb").read())
+    return h.hexdigest()
+
+
+def compare_kinds(torch, iq, hip, w, cfg, args, gen, inner_kernel_ms, stream):
+    """The comparison the paper makes (its Section "Latency": inner grouping against outer grouping and
+    against an unquantised fp16 cache), on this device: the fp16 kernel and the outer-grouped kernel of
+    this library over caches of the same shape, context and value distribution, their fused kernels timed
+    by the same dispatch events as the inner-grouped one."""
+    out = {"inner_kernel_ms": inner_kernel_ms,
+           "paper_context": "the paper reports 2.7x over fp16 and 1.3x over outer grouping (KIVI-style) for its "
+                            "CUDA kernels on an NVIDIA Jetson Xavier NX: other hardware, context only"}
+    B, Hq, d = w.batch, w.n_q_heads, w.head_dim
+    q = torch.randn((B, Hq, d), device="cuda", generator=gen).half()
+    o = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    for kind_name, kind_id in (("fp16", iq.KIND_FP16), ("outer", iq.KIND_OUTER)):
+        c2 = iq.make_config(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.bits, cfg.group, cfg.w_sink,
+                            cfg.w_recent, cfg.k_mode, cfg.v_mode, 0, kind_id,
+                            -(-(w.n_tokens + 2 * w.group) // w.group) * w.group, cfg.v_bits)
+        # enough distinct caches that a call never re-reads what the previous one left in the last-level cache
+        n_inst = 3 if kind_name == "outer" else 2
+        caches = [make_instance(torch, iq, w, c2, i, w.n_tokens, gen) for i in range(n_inst)]
+        ws = iq.allocate_workspace(c2)
+        n = 12 if kind_name == "fp16" else 24
+        evs = [(hip.event(), hip.event()) for _ in range(n)]
+        for i in range(6):
+            iq.innerq_decode_attention(caches[i % n_inst], q, ws, out=o, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            iq.innerq_profile_next_attention(*evs[i])
+            iq.innerq_decode_attention(caches[i % n_inst], q, ws, out=o, stream=stream)
+        torch.cuda.synchronize()
+        call_ms = (time.perf_counter() - t0) / n * 1e3
+        k_ms = sum(hip.elapsed_ms(a, b) for a, b in evs) / n
+        out[f"{kind_name}_kernel_ms"] = k_ms
+        out[f"{kind_name}_attention_call_ms"] = call_ms
+        out[f"inner_speedup_over_{kind_name}"] = k_ms / inner_kernel_ms
+        del caches, ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def prefill_rates(torch, iq, w, cfg, gen):
     """Prefill-side calls on one prompt of the workload's length: calibration reads the fp16 keys
     once; the bulk append reads fp16 keys and values once and writes the packed cache."""
@@ -195,41 +254,68 @@ def prefill_rates(torch, iq, w, cfg, gen):
     }))
 
 
+def host_cores():
+    """Threads the CPU legs may use: the cores this process may run on, at most 16 (the CPU share of one
+    GPU on a shared box, whatever os.cpu_count() shows there)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(n, 16))
+
+
 def cpu_baseline(w, kind_id, seconds, v_bits=0):
-    """The CPU oracle timed on a bounded sample of the same workload: whole (batch, kv-head) slabs,
-    each one decode step (append one token + attention for the slab's query heads)."""
+    """The CPU oracle timed on a bounded sample of the same workload, on all host cores: whole
+    (batch, kv-head) slabs, each one decode step (append one token + attention for the slab's query
+    heads), one slab per thread at a time (numpy releases the interpreter lock inside its array
+    operations; every thread keeps its BLAS single-threaded)."""
+    from concurrent.futures import ThreadPoolExecutor
+
     import numpy as np
     from threadpoolctl import threadpool_limits
 
     from oracle import innerq_oracle as orc
     from paper_2602_23200_amd import workloads as wl
 
+    cores = host_cores()
     r = w.n_q_heads // w.n_kv_heads
-    w1 = w.with_(batch=1, n_kv_heads=1, n_q_heads=r)
     cap = -(-(w.n_tokens + 2 * w.group) // w.group) * w.group
     o = orc.Config(1, r, 1, w.head_dim, w.bits, w.group, w.w_sink, w.w_recent, w.k_mode, w.v_mode, 0,
                    kind_id, cap, v_bits)
     total_slabs = w.batch * w.n_kv_heads * w.n_layers
+    per_layer = w.batch * w.n_kv_heads
+
+    def prepare(i):
+        b, h = divmod(i % per_layer, w.n_kv_heads)
+        k, v = wl.kv_slab(w, b, h, n_tokens=w.n_tokens)
+        cache = orc.cache_init_prefill(o, k[None, None, :-1], v[None, None, :-1])          # not timed: set-up
+        return cache, k[None, None, -1], v[None, None, -1], wl.query(w)[b:b + 1, h * r:(h + 1) * r]
+
+    def step(item):
+        cache, k1, v1, q = item
+        orc.append_token(o, cache, k1, v1)
+        out = orc.decode_attention(o, cache, q)
+        assert np.isfinite(out).all()
+
     done, spent, wall0 = 0, 0.0, time.perf_counter()
-    with threadpool_limits(limits=1):
-        # bounded: stop after `seconds` of timed oracle work or ~4x that of wall-clock (the untimed
-        # set-up of a slab, quantising its prefill, costs more than the timed decode step)
-        while done < total_slabs and spent < seconds and time.perf_counter() - wall0 < 4 * seconds:
-            b, h = divmod(done % (w.batch * w.n_kv_heads), w.n_kv_heads)
-            k, v = wl.kv_slab(w, b, h, n_tokens=w.n_tokens)
-            cache = orc.cache_init_prefill(o, k[None, None, :-1], v[None, None, :-1])      # not timed: setup
-            q = wl.query(w)[b:b + 1, h * r:(h + 1) * r]
+    with threadpool_limits(limits=1), ThreadPoolExecutor(max_workers=cores) as pool:
+        # rounds of `cores` slabs: set-up in parallel (untimed), then the decode step of all of them in
+        # parallel (timed, wall clock).  Bounded: stop after `seconds` of timed work or ~5x that of wall clock.
+        while done < total_slabs and spent < seconds and time.perf_counter() - wall0 < 5 * seconds:
+            n = min(cores, total_slabs - done)
+            items = list(pool.map(prepare, range(done, done + n)))
             t0 = time.perf_counter()
-            orc.append_token(o, cache, k[None, None, -1], v[None, None, -1])
-            out = orc.decode_attention(o, cache, q)
+            list(pool.map(step, items))
             spent += time.perf_counter() - t0
-            assert np.isfinite(out).all()
-            done += 1
+            done += n
+            del items
     step_seconds = spent / done * total_slabs            # one step = every slab of every layer once
-    return {"value": w.batch / step_seconds, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+    return {"value": w.batch / step_seconds, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "host_cpu_count": os.cpu_count(),
             "sample": f"{done} of {total_slabs} (batch, kv-head) slabs of {w.name}, one decode step each "
-                      f"(append + attention, {w.n_tokens} cached tokens), numpy float64, 1 thread, "
-                      f"{spent:.1f} s measured, scaled to the full step"}
+                      f"(append + attention, {w.n_tokens} cached tokens), numpy float64, {cores} threads "
+                      f"(one slab per thread; nproc = {os.cpu_count()}), {spent:.1f} s of wall clock measured, "
+                      f"scaled to the full step"}
 
 
 def main():
@@ -269,8 +355,9 @@ def main():
     K, W = args.steps, args.warmup
     # one cache per layer; single-layer workloads rotate `instances` caches instead
     n_inst = n_layers if n_layers > 1 else max(1, args.instances)
-    per_inst_appends = (-(-(K + W + 3 * K + PREWARM_MAX_STEPS) // n_inst) + 2 if n_layers == 1
-                        else (K + W + 3 * K + PREWARM_MAX_STEPS) + 2)
+    # warm-up, pre-warm, the timed passes, the pass with events, and the breakdown passes (each at most 220 calls)
+    max_steps = W + PREWARM_MAX_STEPS + (K + TIMED_MAX_STEPS) + max(K, 100) + 500
+    per_inst_appends = (-(-max_steps // n_inst) + 2 if n_layers == 1 else max_steps + 2)
     cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
     cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
                          w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits)
@@ -373,19 +460,28 @@ def main():
     for _ in range(W):
         step()
     torch.cuda.synchronize()
+    # timed region: passes of exactly K steps, repeated (without a synchronisation in between) until the
+    # region is long enough to be stable whatever K the caller picked; one host-device synchronisation
+    # on either side
+    repeats = 0
     t0 = time.perf_counter()
-    for _ in range(K):
-        step()
+    while True:
+        for _ in range(K):
+            step()
+        repeats += 1
+        if (time.perf_counter() - t0) * 1e3 >= args.min_timed_ms or (repeats + 1) * K > K + TIMED_MAX_STEPS:
+            break
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) / K * 1e3
+    ms_per_step = (t1 - t0) / (K * repeats) * 1e3
     n_ctx_end = caches[0].n_tokens
 
     # second pass of K steps with HIP events around the dominant kernel of every attention call
-    evs = [[(hip.event(), hip.event()) for _ in range(n_layers)] for _ in range(K)]
+    n_prof = max(K, -(-100 // n_layers))          # at least 100 dispatches, so that a small K gives a stable mean
+    evs = [[(hip.event(), hip.event()) for _ in range(n_layers)] for _ in range(n_prof)]
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    for s in range(K):
+    for s in range(n_prof):
         step(profile=evs[s])
     torch.cuda.synchronize()
     t3 = time.perf_counter()
@@ -396,6 +492,9 @@ def main():
 
     # attention-only and append-only timings (reported, not the headline)
     def time_only(fn, n):
+        n = max(n, 200)                       # the closing synchronisation is amortised over enough calls
+        for _ in range(20):
+            fn()
         torch.cuda.synchronize()
         a = time.perf_counter()
         for _ in range(n):
@@ -413,11 +512,12 @@ def main():
         state["i"] += 1
         iq.innerq_quantize_append(caches[i % n_inst], k_new[i % pool], v_new[i % pool], stream=stream)
 
-    attn_ms = time_only(attn_only, K) * n_layers
-    append_ms = time_only(append_only, K) * n_layers
+    n_break = max(1, min(K, 400) // n_layers)
+    attn_ms = time_only(attn_only, n_break * n_layers) * n_layers
+    append_ms = time_only(append_only, min(n_break * n_layers, 200)) * n_layers
     # the other step mode, for the breakdown (the serial calls also work on caches that were run ahead)
     torch.cuda.synchronize()
-    other_ms = time_only(step_serial, K) if overlapped else None
+    other_ms = time_only(step_serial, max(1, 200 // n_layers)) if overlapped else None
 
     per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
     alg_bytes = per_unit * units
@@ -440,13 +540,25 @@ def main():
     del bufs
     stream_gbs = probe_bytes / (sum(probe_ms) / len(probe_ms) * 1e-3) / 1e9
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (a recorded figure:
-    # counters cannot be read from inside this process); null if this workload was not profiled
-    traffic = None
+    # counters cannot be read from inside this process).  The record names the kernel sources it was
+    # measured with (a hash); it is reported only while those sources are unchanged, else null.
+    traffic, traffic_note = None, "this workload and kernel were not profiled"
     prof_md = os.path.join(ROOT, "profiles", f"attention_{args.kind}_{w.name}_hbm_traffic.md")
     if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits or args.v_bits):
         import re
-        m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(prof_md).read(), re.M)
-        traffic = int(m.group(1)) if m else None
+        text = open(prof_md).read()
+        m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", text, re.M)
+        h = re.search(r"^kernel_sources_sha256:\s*([0-9a-f]+)", text, re.M)
+        now = kernel_sources_sha256(args.kind)
+        if m and h and h.group(1) == now:
+            traffic, traffic_note = int(m.group(1)), f"recorded in profiles/{os.path.basename(prof_md)} for these kernel sources"
+        else:
+            traffic_note = (f"profiles/{os.path.basename(prof_md)} was recorded for other kernel sources "
+                            f"({h.group(1)[:12] if h else 'no hash'} != {now[:12]}): not reported")
+
+    comparison = None
+    if not args.no_comparison and args.kind == "inner" and args.asym_frac is None:
+        comparison = compare_kinds(torch, iq, hip, w, cfg, args, gen, kern_ms, stream)
 
     result = {
         "metric": "decode-attention tokens/s (one attention layer step: append of the new token with its quantisation "
@@ -456,7 +568,8 @@ def main():
                   "achieved HBM GB/s",
         "value": B / (ms_per_step * 1e-3),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "prewarm_steps": prewarm_steps, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": K, "repeats": repeats, "warmup": W, "prewarm_steps": prewarm_steps,
+        "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
@@ -470,7 +583,7 @@ def main():
                    "k_mode": ["sym", "asym", "hybrid"][w.k_mode], "v_mode": ["sym", "asym", "hybrid"][w.v_mode],
                    "layers": n_layers, "cache_instances": n_inst},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
                      "kernel": "fused dequant score+value pass over the quantised range",
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_ms_median,
                      "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_token_kvhead": per_unit,
@@ -478,9 +591,11 @@ def main():
                      "streaming_read_same_bytes": {"achieved": stream_gbs, "unit": "GB/s",
                                                    "frac_of_peak": stream_gbs / HBM_PEAK_GBS,
                                                    "kernel_frac_of_it": achieved / stream_gbs}},
-        "breakdown_ms": {"step": ms_per_step, "step_with_events": (t3 - t2) / K * 1e3,
+        "breakdown_ms": {"step": ms_per_step, "step_with_events": (t3 - t2) / n_prof * 1e3,
                          "attention_only": attn_ms, "append_only": append_ms, "step_serial": other_ms},
     }
+    if comparison is not None:
+        result["comparison"] = comparison
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, kind_id, args.cpu_seconds, args.v_bits)
     print(json.dumps(result))

@@ -12,8 +12,16 @@
  *     memory, never synchronises, and enqueues all its work on the HIP stream
  *     the caller passes (a hipStream_t cast to void*; NULL = the null stream).
  *   - Device pointers must be 16-byte aligned (the kernels use 128-bit loads).
- *   - The library keeps no state between calls: the token counter lives in the
- *     caller's innerq_cache_t (host memory) and is the same for the whole batch.
+ *   - The library keeps no state of a cache between calls: the token counter lives in the
+ *     caller's innerq_cache_t (host memory) and is the same for the whole batch.  What it does
+ *     keep, process-wide and host-side only: the kernel choice set by
+ *     innerq_select_inner_kernel, the one-shot per-thread request of
+ *     innerq_profile_next_attention, remembered answers of occupancy / device-attribute
+ *     queries (atomics; set once), and the device address of the static workspace of
+ *     innerq_decode_attention_static.
+ *   - The exception to "on error nothing has been launched": innerq_decode_step makes two
+ *     launches, and INNERQ_E_HIP from the second one arrives after the first was enqueued
+ *     (every argument check is done before the first).
  *   - Inputs are assumed finite; NaN/Inf in K, V or q give unspecified output.
  *
  * Notation (paper, Sections "KV Caching", "Quantization Scheme"):
@@ -112,6 +120,13 @@ typedef struct {
   void *k_sink, *v_sink;              /* device, may be NULL when w_sink == 0 */
   void *k_recent, *v_recent;          /* device */
   int64_t n_tokens;                   /* host: tokens cached so far; updated by innerq_quantize_append */
+  int64_t store_ahead_tokens;         /* host, maintained by the library: the quantised store holds every row
+                                         that a cache of this many tokens needs.  n_tokens after an ordinary
+                                         append; n_tokens + 1 once the store has been run one step ahead
+                                         (innerq_quantize_ahead, innerq_append_deferred, innerq_decode_step),
+                                         which innerq_decode_attention_next and innerq_decode_step require.
+                                         Zero-initialise it with the struct; to reuse the buffers for a new
+                                         sequence set it and n_tokens back to 0. */
 } innerq_cache_t;
 
 typedef enum {
@@ -232,7 +247,9 @@ int innerq_decode_attention_static(const innerq_config_t *cfg, const innerq_cach
  *   from k_new / v_new (device, fp16 [B][Hk][1][d], keys already normalised if a key norm is
  *   in use) instead of the ring.  Requires that the store already holds what the append of
  *   that token evicts (innerq_quantize_ahead, or the previous innerq_append_deferred).
- *   Does not modify the cache.  Other arguments as innerq_decode_attention.
+ *   Does not modify the cache.  Other arguments as innerq_decode_attention.  INNERQ_E_ARG if
+ *   cache->store_ahead_tokens != n_tokens + 1 (the store was not run ahead: the kernels would
+ *   read rows that were never written).
  * innerq_append_deferred: copies the new token into its window, n_tokens += 1, and does
  *   the innerq_quantize_ahead work for the step after.  It reads the rings and writes one
  *   ring slot and store rows that innerq_decode_attention_next of the same step does not
@@ -255,15 +272,18 @@ int innerq_append_deferred(const innerq_config_t *cfg, innerq_cache_t *cache, co
 /* One decode step in two launches instead of three: innerq_decode_attention_next followed by
  * innerq_append_deferred on the same stream, with the log-sum-exp merge of the attention call
  * and the append sharing one launch (they touch disjoint memory).  Same preconditions, results
- * and errors as those two calls; on success n_tokens += 1 and the store already holds what the
- * next step evicts. */
+ * and errors as those two calls (INNERQ_E_ARG unless store_ahead_tokens == n_tokens + 1); on
+ * success n_tokens += 1 and the store already holds what the next step evicts.  Every argument is
+ * checked before the first launch; only INNERQ_E_HIP of the second launch can follow an enqueued
+ * first one. */
 int innerq_decode_step(const innerq_config_t *cfg, innerq_cache_t *cache, const void *k_new,
                        const void *v_new, const void *q_fp16, const float *q_scale, void *out,
                        int out_is_fp32, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Measurement hook (no counterpart in the paper; its Section "Latency" times the fused
  * dequantise-and-multiply kernels on their own, and this lets a benchmark do the same).
- * The next innerq_decode_attention call made by the calling host thread attaches
+ * The next attention call made by the calling host thread (innerq_decode_attention,
+ * innerq_decode_attention_static, innerq_decode_attention_next or innerq_decode_step) attaches
  * ev_start and ev_stop to the dispatch of its dominant kernel (the fused dequantise +
  * score + value pass over the quantised range) on that call's stream: they take the
  * begin and end timestamps of that dispatch, so their difference is the kernel's own

@@ -34,7 +34,7 @@ class innerq_config_t(C.Structure):
 
 
 class innerq_cache_t(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES] + [("n_tokens", C.c_int64)]
+    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES] + [("n_tokens", C.c_int64), ("store_ahead_tokens", C.c_int64)]
 
 
 class InnerQError(RuntimeError):
@@ -164,6 +164,7 @@ def allocate_cache(cfg: innerq_config_t, device="cuda") -> Cache:
         bufs[name] = torch.zeros(n, dtype=torch.uint8, device=device) if n else None
         setattr(c, name, _ptr(bufs[name]))
     c.n_tokens = 0
+    c.store_ahead_tokens = 0
     return Cache(cfg, bufs, c)
 
 

@@ -90,15 +90,14 @@ TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which,
 
 // Compute units of the current device (queried once per device; a host-side attribute read).
 int compute_units() {
-  static int cached[64] = {0};
+  static CachedInt cached[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
+  return cached[dev].get([&] {
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
+    return n;
+  });
 }
 
 thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
@@ -116,7 +115,7 @@ int innerq_profile_next_attention(void* ev_start, void* ev_stop) {
 
 int innerq_select_inner_kernel(int which) {
   if (which != 0 && which != 1) return INNERQ_E_ARG;
-  g_inner_variant = which;
+  g_inner_variant.store(which, std::memory_order_relaxed);
   return INNERQ_OK;
 }
 
@@ -236,6 +235,7 @@ static int quantize_impl(const innerq_config_t* cfg, innerq_cache_t* cache, cons
   const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream), merge);
   if (e != hipSuccess) return INNERQ_E_HIP;
   cache->n_tokens = n1;
+  cache->store_ahead_tokens = to;
   return INNERQ_OK;
 }
 
@@ -455,6 +455,7 @@ int innerq_decode_attention_next(const innerq_config_t* cfg, const innerq_cache_
   if (!k_new || !v_new) return INNERQ_E_NULL;
   if (misaligned(k_new) || misaligned(v_new)) return INNERQ_E_ALIGN;
   if (cache->n_tokens + 1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  if (cache->store_ahead_tokens != cache->n_tokens + 1) return INNERQ_E_ARG;   // the store was not run one step ahead
   return attention_impl(cfg, cache, cache->n_tokens + 1, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
                         workspace_bytes, hip_stream);
 }
@@ -469,6 +470,7 @@ int innerq_decode_step(const innerq_config_t* cfg, innerq_cache_t* cache, const 
   if (!k_new || !v_new) return INNERQ_E_NULL;
   if (misaligned(k_new) || misaligned(v_new)) return INNERQ_E_ALIGN;
   if (cache->n_tokens + 1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  if (cache->store_ahead_tokens != cache->n_tokens + 1) return INNERQ_E_ARG;   // the store was not run one step ahead
   AttnArgs merge;
   st = attention_impl(cfg, cache, cache->n_tokens + 1, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
                       workspace_bytes, hip_stream, &merge);

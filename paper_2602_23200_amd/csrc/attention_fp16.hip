@@ -187,16 +187,14 @@ bool attention_fp16_supported(const AttnArgs& a) {
 }
 
 int attention_fp16_waves_per_cu(const AttnArgs& a) {
-  static int cache[2] = {0, 0};
+  static CachedInt cache[2];
   const int r = a.n_q_heads / a.n_kv_heads;
-  int& c = cache[r > 4];
-  if (c == 0) {
+  return cache[r > 4].get([&] {
     int n = 0;
     const hipError_t e = r <= 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_fp16_kernel<1>, 64, 0)
                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_fp16_kernel<2>, 64, 0);
-    c = (e == hipSuccess && n > 0) ? n : 4;
-  }
-  return c;
+    return (e == hipSuccess && n > 0) ? n : 4;
+  });
 }
 
 hipError_t launch_attention_fp16(const AttnArgs& a, long long n_rows, int n_splits, const WindowSet& win,

@@ -705,24 +705,24 @@ struct LaunchFn {
   hipError_t operator()() const { return launch_t<KB, VB, G>(a, n_both, n_splits, win, L); }
 };
 
-int g_inner_variant = 0;
+std::atomic<int> g_inner_variant{0};
 
 int attention_inner_waves_per_cu(const AttnArgs& a) {
-  if (g_inner_variant == 1 && attention_inner_f4_supported(a)) return attention_inner_f4_waves_per_cu(a);
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
+    return attention_inner_f4_waves_per_cu(a);
   // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
-  static int cache[4][2][2][2][2] = {};
+  static CachedInt cache[4][2][2][2][2];
   const int r = a.n_q_heads / a.n_kv_heads;
   const int wp = width_pair(a);
   if (wp < 0) return 8;
-  int& c = cache[wp][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4];
-  if (c == 0) c = for_widths(a, ResidentFn{a});
-  return c;
+  return cache[wp][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4].get(
+      [&] { return for_widths(a, ResidentFn{a}); });
 }
 
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!attention_inner_supported(a)) return hipErrorInvalidValue;
-  if (g_inner_variant == 1 && attention_inner_f4_supported(a))
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
     return launch_attention_inner_f4(a, n_both_ll, n_splits, win, stream, ev_start, ev_stop);
   const Launch L = {stream, ev_start, ev_stop};
   return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});

@@ -619,10 +619,9 @@ bool attention_inner_f4_supported(const AttnArgs& a) {
 }
 
 int attention_inner_f4_waves_per_cu(const AttnArgs& a) {
-  static int cache[2][2][2] = {};
-  int& c = cache[a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr];
-  if (c == 0) c = a.group == 32 ? resident_g<32>(a) : resident_g<64>(a);
-  return c;
+  static CachedInt cache[2][2][2];
+  return cache[a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr].get(
+      [&] { return a.group == 32 ? resident_g<32>(a) : resident_g<64>(a); });
 }
 
 hipError_t launch_attention_inner_f4(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,

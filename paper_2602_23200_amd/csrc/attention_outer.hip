@@ -312,14 +312,13 @@ bool attention_outer_supported(const AttnArgs& a) {
 int attention_outer_waves_per_cu(const AttnArgs& a) {
   // 64-thread groups, about 26 KB of LDS each: the LDS budget of a compute unit decides
   (void)a;
-  static int c = 0;
-  if (c == 0) {
+  static CachedInt c;
+  return c.get([] {
     int n = 0;
     const hipError_t e =
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_outer_kernel<2, 32, 1, true, true>, 64, 0);
-    c = (e == hipSuccess && n > 0) ? n : 4;
-  }
-  return c;
+    return (e == hipSuccess && n > 0) ? n : 4;
+  });
 }
 
 hipError_t launch_attention_outer(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,

@@ -7,6 +7,8 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/innerq.h"
 
 namespace innerq {
@@ -139,7 +141,20 @@ bool attention_inner_f4_supported(const AttnArgs& a);
 int attention_inner_f4_waves_per_cu(const AttnArgs& a);
 hipError_t launch_attention_inner_f4(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                      hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
-extern int g_inner_variant;   // 0: 4x4x4 fp16 form everywhere (default); 1: fp8 x fp4 form where it applies
+extern std::atomic<int> g_inner_variant;   // 0: 4x4x4 fp16 form everywhere (default); 1: fp8 x fp4 form where it applies
+
+// A host-side answer that depends on the kernel instance only (an occupancy query, a device attribute),
+// looked up once and kept: relaxed atomics, so that concurrent first callers race benignly (both store
+// the same value).  0 = not asked yet.
+struct CachedInt {
+  std::atomic<int> v{0};
+  template <typename F>
+  int get(F ask) {
+    int x = v.load(std::memory_order_relaxed);
+    if (x == 0) { x = ask(); v.store(x, std::memory_order_relaxed); }
+    return x;
+  }
+};
 
 // Comparison kernel over an unquantised fp16 store, same launch shape.
 bool attention_fp16_supported(const AttnArgs& a);

@@ -45,7 +45,8 @@ def test_struct_layout_matches_header_order():
     # twelve int32, one int64, one int32 (+ tail padding to the int64 alignment)
     assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8 + 8
     assert iq.innerq_config_t.capacity_tokens.offset == 48 and iq.innerq_config_t.v_bits.offset == 56
-    assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8
+    assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8 + 8
+    assert iq.innerq_cache_t.store_ahead_tokens.offset == 88
 
 
 def test_validate_config_rejections():
@@ -127,6 +128,14 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert L.innerq_quantize_append(C.byref(c), C.byref(cache), 4097, 4096, 1, None, None) == iq.E_ALIGN
     assert L.innerq_decode_attention(C.byref(c), C.byref(cache), 4096, None, 4096, 1, 4096, 8, None) == iq.E_WORKSPACE
     assert L.innerq_decode_attention(C.byref(c), C.byref(cache), 4098, None, 4096, 1, 4096, 1 << 30, None) == iq.E_ALIGN
+    # the one-step-ahead calls refuse a cache whose store was not run ahead (nothing records it otherwise,
+    # and the kernels would read store rows that were never written)
+    cache.store_ahead_tokens = 10
+    assert L.innerq_decode_attention_next(C.byref(c), C.byref(cache), 4096, 4096, 4096, None, 4096, 1, 4096,
+                                          1 << 30, None) == iq.E_ARG
+    assert L.innerq_decode_step(C.byref(c), C.byref(cache), 4096, 4096, 4096, None, 4096, 1, 4096, 1 << 30,
+                                None) == iq.E_ARG
+    assert cache.n_tokens == 10 and cache.store_ahead_tokens == 10
     cache.n_tokens = 0
     assert L.innerq_decode_attention(C.byref(c), C.byref(cache), 4096, None, 4096, 1, 4096, 1 << 30, None) == iq.E_ARG
     cache.k_scales = 4104

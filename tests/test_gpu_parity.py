@@ -771,3 +771,110 @@ def test_deferred_calls_on_a_full_cache(env):
     with pytest.raises(iq.InnerQError):
         iq.innerq_decode_step(g, k1, v1, q, ws)
     assert g.n_tokens == 96
+
+
+def _decode_steps_full_size(torch, iq, w, o, Kd, Vd, keep, n_prompt, n_steps, check_at, layer=0, inv=None, norm=None):
+    """Bulk prompt of n_prompt tokens (already on the device as Kd, Vd, which hold all n_prompt + n_steps
+    tokens), innerq_quantize_ahead, then n_steps innerq_decode_step calls: the path the benchmark times.
+    The oracle follows the sampled (batch, kv-head) slabs in `keep` token by token; outputs are compared at
+    the steps in check_at, the cache of every sampled slab at the end."""
+    B, Hk, d = w.batch, w.n_kv_heads, w.head_dim
+    r = w.n_q_heads // w.n_kv_heads
+    o1 = oracle_config(w.with_(batch=1, n_kv_heads=1, n_q_heads=r), capacity=o.capacity_tokens)
+    g = iq.allocate_cache(gpu_config(o))
+    inv_d = None if inv is None else to_dev(torch, inv)
+    iq.innerq_quantize_append(g, Kd[:, :, :n_prompt].contiguous(), Vd[:, :, :n_prompt].contiguous(), k_inv_norm=inv_d)
+    ws = iq.allocate_workspace(g.cfg)
+    k1 = Kd[:, :, n_prompt:n_prompt + 1].contiguous()
+    q0 = to_dev(torch, wl.query(w, layer, 0))
+    with pytest.raises(iq.InnerQError):                 # the store has not been run ahead yet
+        iq.innerq_decode_step(g, k1, k1, q0, ws)
+    assert g.n_tokens == n_prompt
+    iq.innerq_quantize_ahead(g)
+    want = {}
+    for (b, h), (k, v) in keep.items():
+        want[(b, h)] = orc.cache_init_prefill(o1, k[None, None, :n_prompt], v[None, None, :n_prompt],
+                                              k_inv_norm=None if inv is None else inv[h:h + 1])
+    scale = None if norm is None else to_dev(torch, norm)
+    # keys that arrive during decoding have the factors folded in already (the projection carries them)
+    if inv is not None:
+        Kd[:, :, n_prompt:] = (Kd[:, :, n_prompt:].float() * inv_d[None, :, None, :]).half()
+    for i in range(n_steps):
+        t = n_prompt + i
+        q = wl.query(w, layer, i)
+        out = iq.innerq_decode_step(g, Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous(),
+                                    to_dev(torch, q), ws, q_scale=scale)
+        for (b, h), (k, v) in keep.items():
+            kn = k[None, None, t:t + 1] if inv is None else orc.apply_channel_scale(k[None, None, t:t + 1], inv[h:h + 1])
+            orc.quantize_append(o1, want[(b, h)], kn, v[None, None, t:t + 1])
+        if i in check_at:
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all()
+            for (b, h) in keep:
+                ref = orc.decode_attention(o1, want[(b, h)], q[b:b + 1, h * r:(h + 1) * r],
+                                           q_scale=None if norm is None else norm[h:h + 1])
+                assert max_rel_err(got[b:b + 1, h * r:(h + 1) * r], ref) <= TOL, f"step {i} slab {b},{h}"
+    torch.cuda.synchronize()
+    assert g.n_tokens == n_prompt + n_steps
+    for (b, h) in keep:
+        assert_cache_equal(g, want[(b, h)], o1, bsel=slice(b, b + 1), hsel=slice(h, h + 1), what=f"slab {b},{h}")
+
+
+@pytest.mark.parametrize("name,slabs,n_steps", [("llama3_8b_32k", [(0, 0), (3, 5), (7, 7)], 72),
+                                                 ("mistral_7b_8k", [(0, 0), (17, 3), (31, 7)], 132)])
+def test_decode_step_full_size_sampled(env, name, slabs, n_steps):
+    """The path the benchmark times, at the benchmark's size and launch shape: a whole prompt appended
+    in bulk, the store run one step ahead, then single-token innerq_decode_step calls across two value
+    spills.  Three (batch, kv-head) slabs are followed by the oracle: outputs within tolerance at the
+    first step, after each spill and at the end; packed bytes, flags and windows bit-exact at the end."""
+    torch, iq = env
+    w = wl.WORKLOADS[name]
+    B, Hk, N, d, G = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim, w.group
+    n_prompt = N - n_steps
+    o = oracle_config(w)
+    Kd = torch.empty((B, Hk, N, d), dtype=torch.float16, device="cuda")
+    Vd = torch.empty_like(Kd)
+    keep = {}
+    for b in range(B):
+        for h in range(Hk):
+            k, v = wl.kv_slab(w, b, h)
+            Kd[b, h].copy_(torch.from_numpy(k))
+            Vd[b, h].copy_(torch.from_numpy(v))
+            if (b, h) in slabs:
+                keep[(b, h)] = (k, v)
+    # steps at which a value group has just been spilled: the token count minus the windows is a multiple of G
+    spills = [i for i in range(n_steps) if (n_prompt + i + 1 - w.w_sink - w.w_recent) % G == 0]
+    assert len(spills) >= 2
+    check_at = sorted({0, spills[0], spills[0] + 1, spills[1], n_steps - 1})
+    _decode_steps_full_size(torch, iq, w, o, Kd, Vd, keep, n_prompt, n_steps, check_at)
+
+
+def test_decode_step_long_context_layer_full_size_sampled(env):
+    """One layer of the 128k-token configuration driven the way the benchmark drives it: key factors
+    calibrated over the prompt and folded (prompt keys divided on their way in, later keys arrive
+    divided, the query multiplied in the kernel), then innerq_decode_step calls across a value spill."""
+    torch, iq = env
+    w = wl.WORKLOADS["llama3_8b_128k_32L"]
+    layer, n_steps = 7, 40
+    B, Hk, N, d, G = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim, w.group
+    n_prompt = N - n_steps
+    o = oracle_config(w)
+    slabs = [(1, 2), (3, 7)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2000 + layer)
+    sigma = to_dev(torch, wl.key_channel_sigma(w, layer).astype(np.float32))
+    Kd = (torch.randn((B, Hk, N, d), device="cuda", generator=gen) * sigma[None, :, None, :]).half()
+    Vd = torch.randn((B, Hk, N, d), device="cuda", generator=gen).half()
+    keep = {}
+    for (b, h) in slabs:
+        k, v = wl.kv_slab(w, b, h, layer)
+        Kd[b, h].copy_(torch.from_numpy(k))
+        Vd[b, h].copy_(torch.from_numpy(v))
+        keep[(b, h)] = (k, v)
+    peak = Kd[:, :, :n_prompt].abs().amax(dim=(0, 2)).cpu().numpy()[None, :, None, :]
+    norm, inv = orc.calibrate_key_norm(peak, per_head=False)
+    spills = [i for i in range(n_steps) if (n_prompt + i + 1 - w.w_sink - w.w_recent) % G == 0]
+    assert spills
+    check_at = sorted({0, spills[0], n_steps - 1})
+    _decode_steps_full_size(torch, iq, w, o, Kd, Vd, keep, n_prompt, n_steps, check_at, layer=layer, inv=inv, norm=norm)
