@@ -3,12 +3,23 @@
 // token -- the layout the paper compares against, Figure "inner_outer" (a)).
 //
 // Same skeleton as the inner-grouped and fp16 kernels (one wavefront per token range, 64-token
-// tiles, register prefetch of the next tile, window wavefronts in the same launch, same merge).
-// What differs is forced by the grouping: along the inner dimension of q.K^T every channel of a
-// key row has its own scale and zero-point, so nothing factors out of the inner sum and every
-// element is dequantised (Eq. asym_dequant) before it is multiplied; the packed key codes are
-// token-minor, so the dequantised tile goes through LDS to reach the one-token-per-lane score
-// pass.  Values are dequantised element by element on their way into the value pass.
+// tiles, register prefetch of the next tile, window wavefronts in the same launch, same merge), and
+// the multiply-accumulates run on the same 4x4x4 fp16 matrix instructions.  What differs is forced
+// by the grouping.  Along the inner dimension of q.K^T every channel of a key row has its own scale
+// and zero-point, and along the inner dimension of p.V every token has its own: nothing factors out
+// of an inner sum, so every element is dequantised (Eq. asym_dequant) to fp16 before it meets the
+// matrix cores.  And the packing runs across the inner dimension instead of along it (a key word
+// holds 16 tokens of ONE channel, a value word 16 channels of ONE token), so the fields of one inner
+// sum never sit in one lane: the dequantised keys go through an LDS tile to reach the
+// one-token-per-lane score pass, the value rows through an LDS staging area to reach the
+// channel-per-lane value pass.
+// Dequantisation costs two vector instructions per element: a field moved to mantissa bits 8..9 (6..9
+// for 4-bit codes) of an fp16 number with a fixed exponent reads as bias + u (bias 4, resp. 16), two
+// fields per 32-bit instruction; a packed subtract takes the bias off (exactly) and one packed fp16
+// fused multiply-add forms S * u + Zeff for both, rounded once: the correctly rounded fp16 value of
+// the dequantised element.  (Folding the bias into the constant, S * (bias + u) + (Zeff - bias * S),
+// saves the subtract but rounds a constant several times larger than the element: 1e-2 on the
+// output with heavy-tailed keys, measured.)
 #include "innerq_dev.h"
 #include "window_pass.h"
 
@@ -25,14 +36,9 @@ constexpr int D = kHeadDim;
 constexpr int TILE = 64;
 constexpr int KROW = D + 8;                 // padded LDS row of the dequantised key tile (halves)
 
-__device__ inline float wave_max_o(float x) {
-  for (int off = 32; off; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-  return x;
-}
-__device__ inline float wave_sum_o(float x) {
-  for (int off = 32; off; off >>= 1) x += __shfl_xor(x, off);
-  return x;
-}
+// wave-wide reductions: the DPP forms shared with the window pass
+__device__ inline float wave_max_o(float x) { return window_wave_max(x); }
+__device__ inline float wave_sum_o(float x) { return window_wave_sum(x); }
 __device__ inline float half_lo(uint32_t p) { return __half2float(__ushort_as_half((unsigned short)(p & 0xffffu))); }
 __device__ inline float half_hi(uint32_t p) { return __half2float(__ushort_as_half((unsigned short)(p >> 16))); }
 
@@ -48,6 +54,33 @@ struct OuterRegs {
   uint32_t vs[NG / 2], vz[NG / 2];                     // fp16 pairs
 };
 
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
+// Two b-bit fields (one in each 16-bit half of w, at bit `at` of its half) as the fp16 pair (u, u'):
+// the field lands on the top mantissa bits under a fixed exponent, which reads as bias + u.
+template <int BITS>
+__device__ __forceinline__ half2_t fields_as_half2(uint32_t w, int at) {
+  constexpr int TOP = 10 - BITS;                           // first mantissa bit the field occupies
+  constexpr uint32_t MASK = (((1u << BITS) - 1u) << TOP) * 0x00010001u;
+  constexpr uint32_t EXPO = (BITS == 2 ? 0x4400u : 0x4C00u) * 0x00010001u;    // 4.0 resp. 16.0
+  constexpr _Float16 BIAS = BITS == 2 ? (_Float16)4.0f : (_Float16)16.0f;
+  const uint32_t moved = at < TOP ? w << (TOP - at) : w >> (at - TOP);
+  return __builtin_bit_cast(half2_t, (moved & MASK) | EXPO) - half2_t{BIAS, BIAS};
+}
+
+// (|S|, Zeff) of one group as an fp16 pair; Zeff = Z for an asymmetric group (scale sign bit set),
+// -2^(b-1) |S| for a symmetric one (Eq. hybrid_dequant).
+template <int BITS, bool HASZ>
+__device__ __forceinline__ half2_t scale_and_offset(float sc, float zp) {
+  const float S = fabsf(sc);
+  float z = -S * (float)(1 << (BITS - 1));
+  if constexpr (HASZ) z = (__float_as_uint(sc) >> 31) ? zp : z;
+  half2_t r;
+  r[0] = (_Float16)S;
+  r[1] = (_Float16)z;
+  return r;
+}
+
 template <int BITS, int G, int NH4, bool ZK, bool ZV>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
@@ -55,10 +88,10 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   constexpr int NH = NH4 * 4;
   constexpr int GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC, NG = Regs::NG;
   constexpr int FPW = 32 / BITS;
+  constexpr int HALF = FPW / 2;                        // fields per 16-bit half of a word
   constexpr int WPG = G / FPW;                         // words per channel of one key group
-  constexpr uint32_t FMASK = (1u << BITS) - 1u;
-  constexpr float HALFCODE = (float)(1 << (BITS - 1));
   constexpr int ROWB = D * BITS / 8;
+  constexpr int ROWW = ROWB / 4;                       // words of one packed value row
 
   const int lane = threadIdx.x;
   const long long bh = blockIdx.y;
@@ -75,11 +108,12 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   const int t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
   const int t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
 
-  __shared__ __attribute__((aligned(16))) _Float16 qs[NH][D];
+  __shared__ __attribute__((aligned(16))) _Float16 qs[NH][D];           // query, fp16 (exact)
   __shared__ __attribute__((aligned(16))) _Float16 kt[TILE][KROW];      // dequantised keys, token-major
-  __shared__ __attribute__((aligned(16))) float wp[TILE][NH];
-  __shared__ __attribute__((aligned(16))) uint32_t vcode[TILE][ROWB / 4 + 1];   // packed value rows (padded)
-  __shared__ __attribute__((aligned(16))) float2_t vsz[TILE][NG];       // (|S|, Zeff) of each value group
+  // probabilities of the tile, rounded to fp16, as matrix operands: [token % 4][head][token / 4]
+  __shared__ __attribute__((aligned(16))) _Float16 wp16[4 * NH * 16];
+  __shared__ __attribute__((aligned(16))) uint32_t vcode[TILE][ROWW + 1];   // packed value rows (padded)
+  __shared__ __attribute__((aligned(16))) half2_t vsz[TILE][NG];        // (|S|, Zeff) of each value group
 
   for (int i = lane; i < NH * D; i += 64) {
     const int h = i / D, c = i % D;
@@ -131,14 +165,18 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   };
 
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;
-  float m_run[NH], l_run[NH], o[NH][8];
+  // oq[e][n]: channel 8 cg + e of this lane, heads 4 n .. 4 n + 3, the tokens 4 k + tg of every tile
+  float m_run[NH], l_run[NH];
+  float4_t oq[8][NH4];
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
     m_run[h] = -INFINITY;
     l_run[h] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int n = 0; n < NH4; ++n) oq[e][n] = float4_t{0.f, 0.f, 0.f, 0.f};
   const int cg = lane & 15, tg = lane >> 4;
 
   Regs cur, nxt;
@@ -147,32 +185,29 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
     if (tile + 1 < t1) load_tile(tile + 1, nxt);       // in flight while this tile is computed
     __syncthreads();                                   // previous tile's readers of the LDS tiles are done
 
-    // ---- dequantise this lane's two key channels of all 64 tokens into the token-major tile
+    // ---- dequantise this lane's two key channels of all 64 tokens into the token-major tile: a word
+    // holds 2 x HALF tokens of one channel, so one instruction handles tokens (p, HALF + p) of it
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
-      const uint32_t sp = cur.ks[gi];
-      const float S0 = fabsf(half_lo(sp)), S1 = fabsf(half_hi(sp));
-      float z0 = -S0 * HALFCODE, z1 = -S1 * HALFCODE;
-      if constexpr (ZK) {
-        const uint32_t zp = cur.kz[gi];
-        z0 = ((sp >> 15) & 1u) ? half_lo(zp) : z0;
-        z1 = (sp >> 31) ? half_hi(zp) : z1;
-      }
+      const uint32_t sp = cur.ks[gi], zp = ZK ? cur.kz[gi] : 0u;
+      const half2_t sz0 = scale_and_offset<BITS, ZK>(half_lo(sp), half_lo(zp));
+      const half2_t sz1 = scale_and_offset<BITS, ZK>(half_hi(sp), half_hi(zp));
+      const half2_t S0 = {sz0[0], sz0[0]}, Z0 = {sz0[1], sz0[1]}, S1 = {sz1[0], sz1[0]}, Z1 = {sz1[1], sz1[1]};
 #pragma unroll
       for (int wd = 0; wd < WPG; ++wd) {
         const uint32_t w0 = cur.kc[gi][wd / 4][wd % 4], w1 = cur.kc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
 #pragma unroll
-        for (int e = 0; e < FPW; ++e) {
-          const float x0 = S0 * (float)((w0 >> (e * BITS)) & FMASK) + z0;
-          const float x1 = S1 * (float)((w1 >> (e * BITS)) & FMASK) + z1;
-          half2_t hx;
-          hx[0] = (_Float16)x0;
-          hx[1] = (_Float16)x1;
-          *reinterpret_cast<half2_t*>(&kt[gi * G + wd * FPW + e][2 * lane]) = hx;
+        for (int p = 0; p < HALF; ++p) {
+          const half2_t x0 = __builtin_elementwise_fma(fields_as_half2<BITS>(w0, p * BITS), S0, Z0);   // channel 2 lane: tokens p, HALF + p
+          const half2_t x1 = __builtin_elementwise_fma(fields_as_half2<BITS>(w1, p * BITS), S1, Z1);   // channel 2 lane + 1
+          const uint32_t u0 = __builtin_bit_cast(uint32_t, x0), u1 = __builtin_bit_cast(uint32_t, x1);
+          const int tok = gi * G + wd * FPW + p;
+          *reinterpret_cast<uint32_t*>(&kt[tok][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x05040100u);          // low halves
+          *reinterpret_cast<uint32_t*>(&kt[tok + HALF][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x07060302u);   // high halves
         }
       }
     }
-    // ---- stage this lane's packed value row and its group scales
+    // ---- stage this lane's packed value row and its group constants
 #pragma unroll
     for (int i = 0; i < VC; ++i) {
       vcode[lane][4 * i + 0] = cur.vc[i].x;
@@ -182,82 +217,112 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
     }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const uint32_t sp = cur.vs[g / 2];
-      const float sc = (g & 1) ? half_hi(sp) : half_lo(sp);
-      const float S = fabsf(sc);
-      float z = -S * HALFCODE;
-      if constexpr (ZV) {
-        const uint32_t zp = cur.vz[g / 2];
-        const bool asym = (g & 1) ? (sp >> 31) : ((sp >> 15) & 1u);
-        z = asym ? ((g & 1) ? half_hi(zp) : half_lo(zp)) : z;
-      }
-      vsz[lane][g] = float2_t{S, z};
+      const uint32_t sp = cur.vs[g / 2], zp = ZV ? cur.vz[g / 2] : 0u;
+      vsz[lane][g] = scale_and_offset<BITS, ZV>((g & 1) ? half_hi(sp) : half_lo(sp), (g & 1) ? half_hi(zp) : half_lo(zp));
     }
     __syncthreads();
 
-    // ---- scores: lane = token (Eq. att:1)
+    // ---- scores: lane = token (Eq. att:1), 4x4x4 blocks: B = four consecutive channels of the lane's
+    // dequantised row, A = the same channels of four heads
     float s[NH];
+    {
+      float4_t sacc[NH4];
 #pragma unroll
-    for (int h = 0; h < NH; ++h) s[h] = 0.f;
-#pragma unroll 4
-    for (int i = 0; i < D / 8; ++i) {
-      const u32x4 kv = *reinterpret_cast<const u32x4*>(&kt[lane][i * 8]);
-      const uint32_t kw[4] = {kv.x, kv.y, kv.z, kv.w};
+      for (int n = 0; n < NH4; ++n) sacc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int h = 0; h < NH; ++h) {
-        const u32x4 qv = *reinterpret_cast<const u32x4*>(&qs[h][i * 8]);
-        const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+      for (int i = 0; i < D / 8; ++i) {
+        const u32x4 kv = *reinterpret_cast<const u32x4*>(&kt[lane][i * 8]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const half2_t kk = __builtin_bit_cast(half2_t, kw[e]), qq = __builtin_bit_cast(half2_t, qw[e]);
-          s[h] += (float)kk[0] * (float)qq[0];
-          s[h] += (float)kk[1] * (float)qq[1];
+        for (int hf = 0; hf < 2; ++hf) {
+          u32x2 bw;
+          bw.x = hf ? kv.z : kv.x;
+          bw.y = hf ? kv.w : kv.y;
+          const half4_t bop = __builtin_bit_cast(half4_t, bw);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const half4_t aop = *reinterpret_cast<const half4_t*>(&qs[4 * n + (lane & 3)][8 * i + 4 * hf]);
+            sacc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, sacc[n], 0, 0, 0);
+          }
         }
       }
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+        s[4 * n] = sacc[n].x; s[4 * n + 1] = sacc[n].y; s[4 * n + 2] = sacc[n].z; s[4 * n + 3] = sacc[n].w;
+      }
     }
-    // ---- running softmax (Eq. att:2)
+    // ---- running softmax (Eq. att:2); the weights are rounded to fp16 for the matrix cores and the
+    // normaliser is formed from the rounded weights
     const bool valid = tile * TILE + lane <= last_row;
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
       const float sv = valid ? s[h] * c_log2 : -INFINITY;
       const float m_new = fmaxf(m_run[h], wave_max_o(sv));
       const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);
-      const float p = __builtin_amdgcn_exp2f(sv - m_new);
-      l_run[h] = l_run[h] * alpha + wave_sum_o(p);
+      const _Float16 p16 = (_Float16)__builtin_amdgcn_exp2f(sv - m_new);
+      wp16[((lane & 3) * NH + h) * 16 + (lane >> 2)] = p16;
+      l_run[h] = l_run[h] * alpha + wave_sum_o((float)p16);
       m_run[h] = m_new;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[h][e] *= alpha;
-      wp[lane][h] = p;
+      for (int e = 0; e < 8; ++e) oq[e][h / 4][h % 4] *= alpha;
     }
     __syncthreads();
-    // ---- values: lane = 8 channels of tokens 4i + tg, dequantised on the way (Eq. att:3)
+    // ---- values (Eq. att:3): lane = 8 channels (8 cg ..) of the tokens 4 k + tg; every row chunk is
+    // dequantised to four fp16 pairs, then four rows give the B operands (one channel of four tokens)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int j = 4 * i + tg;
-      // the 8 fields of channels 8cg .. 8cg+7: 8*BITS bits at bit offset 8*cg*BITS of the row
-      uint32_t bitsw;
-      if constexpr (BITS == 2) bitsw = (vcode[j][cg / 2] >> ((cg & 1) * 16)) & 0xffffu;
-      else bitsw = vcode[j][cg];
-      const float2_t sz = vsz[j][(8 * cg) / G];
-      float x[8];
+    for (int kq = 0; kq < 4; ++kq) {
+      half4_t aop[NH4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = sz[0] * (float)((bitsw >> (e * BITS)) & FMASK) + sz[1];
+      for (int n = 0; n < NH4; ++n)
+        aop[n] = *reinterpret_cast<const half4_t*>(&wp16[(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
+      uint32_t x[4][4];                                  // [row][pair]: dequantised fp16 pairs
 #pragma unroll
-      for (int n = 0; n < NH4; ++n) {
-        const float4_t pj = *reinterpret_cast<const float4_t*>(&wp[j][n * 4]);
+      for (int i = 0; i < 4; ++i) {
+        const int j = 4 * (4 * kq + i) + tg;
+        const half2_t sz = vsz[j][(8 * cg) / G];
+        const half2_t S = {sz[0], sz[0]}, Z = {sz[1], sz[1]};
+        if constexpr (BITS == 2) {
+          // 8 fields in 16 bits: low half = the chunk, high half = the chunk >> 2, so that pair e holds
+          // fields 2 e (low half) and 2 e + 1 (high half) at bit 4 e of their halves
+          const uint32_t c16 = (vcode[j][cg / 2] >> ((cg & 1) * 16)) & 0xffffu;
+          const uint32_t w = (c16 << 14) | c16;
 #pragma unroll
-        for (int hh = 0; hh < 4; ++hh)
+          for (int e = 0; e < 4; ++e)
+            x[i][e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(fields_as_half2<2>(w, 4 * e), S, Z));
+        } else {
+          // 8 fields in 32 bits: pair e holds fields e (low half) and e + 4 (high half) at bit 4 e
+          const uint32_t w = vcode[j][cg];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[n * 4 + hh][e] += pj[hh] * x[e];
+          for (int e = 0; e < 4; ++e)
+            x[i][e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(fields_as_half2<4>(w, 4 * e), S, Z));
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        u32x2 lo, hi;
+        lo.x = __builtin_amdgcn_perm(x[1][e], x[0][e], 0x05040100u);   // low halves of rows 0, 1
+        lo.y = __builtin_amdgcn_perm(x[3][e], x[2][e], 0x05040100u);
+        hi.x = __builtin_amdgcn_perm(x[1][e], x[0][e], 0x07060302u);   // high halves
+        hi.y = __builtin_amdgcn_perm(x[3][e], x[2][e], 0x07060302u);
+        const half4_t blo = __builtin_bit_cast(half4_t, lo), bhi = __builtin_bit_cast(half4_t, hi);
+        // channel of the low / high half of pair e (see the two packings above)
+        constexpr int STEP = BITS == 2 ? 1 : 4;
+        const int c_lo = BITS == 2 ? 2 * e : e, c_hi = c_lo + STEP;
+#pragma unroll
+        for (int n = 0; n < NH4; ++n) {
+          oq[c_lo][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], blo, oq[c_lo][n], 0, 0, 0);
+          oq[c_hi][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], bhi, oq[c_hi][n], 0, 0, 0);
+        }
       }
     }
     cur = nxt;
   }
 
+  float o[NH][8];
 #pragma unroll
   for (int h = 0; h < NH; ++h)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
+      o[h][e] = oq[e][h / 4][h % 4];
       o[h][e] += __shfl_xor(o[h][e], 16);
       o[h][e] += __shfl_xor(o[h][e], 32);
     }
