@@ -62,6 +62,9 @@ def parse():
                    help="fill the caches with crafted groups of which a fraction F is quantised asymmetrically "
                         "in hybrid mode (the rest symmetrically): the density sweep of the flag matrix "
                         "(paper, Section 'Sparsity of M')")
+    p.add_argument("--sparse-zeros", action="store_true",
+                   help="value zero-points are read only where a group is flagged asymmetric "
+                        "(innerq_config_t.sparse_zeros = 1)")
     p.add_argument("--prefill", action="store_true",
                    help="time the prefill-side calls instead (key-norm calibration and the bulk append that "
                         "quantises a whole prompt) and print their rates; exits without the decode loop")
@@ -103,9 +106,11 @@ class Hip:
         return ms.value
 
 
-def algorithmic_bytes(w, cfg, iq, n_tokens):
+def algorithmic_bytes(w, cfg, iq, n_tokens, v_asym_frac=None):
     """Bytes the method itself must move per attention call over the quantised range:
-    per cached (token, kv-head) K + V codes, fp16 scales and (unless symmetric) fp16 zero-points."""
+    per cached (token, kv-head) K + V codes, fp16 scales and (unless symmetric) fp16 zero-points.
+    A kernel that reads zero-points only for asymmetric groups (sparse_zeros) is charged the
+    asymmetric fraction of the dense zero-point bytes."""
     nq_k = iq.innerq_partition(cfg, 0, n_tokens)[1]
     nq_v = iq.innerq_partition(cfg, 1, n_tokens)[1]
     n_both = min(nq_k, nq_v)
@@ -114,8 +119,11 @@ def algorithmic_bytes(w, cfg, iq, n_tokens):
         per_unit = 2 * d * 2
     else:
         per_unit = 0
-        for mode, bits in ((cfg.k_mode, cfg.bits), (cfg.v_mode, cfg.v_bits or cfg.bits)):
-            per_unit += d * bits // 8 + (d // G) * 2 * (1 if mode == iq.SYM else 2)
+        for which, mode, bits in ((0, cfg.k_mode, cfg.bits), (1, cfg.v_mode, cfg.v_bits or cfg.bits)):
+            zero_share = 0.0 if mode == iq.SYM else 1.0
+            if which == 1 and cfg.sparse_zeros and cfg.kind == iq.KIND_INNER and v_asym_frac is not None:
+                zero_share *= v_asym_frac
+            per_unit += d * bits // 8 + (d // G) * 2 * (1 + zero_share)
     units = w.batch * w.n_kv_heads * n_both
     return per_unit, units
 
@@ -360,7 +368,7 @@ def main():
     per_inst_appends = (-(-max_steps // n_inst) + 2 if n_layers == 1 else max_steps + 2)
     cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
     cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
-                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits)
+                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits, int(args.sparse_zeros))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
     if args.prefill:
@@ -370,7 +378,7 @@ def main():
               for i in range(n_inst)]
     B, Hq, Hk, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
     flag_density = None
-    if args.asym_frac is not None and kind_id != iq.KIND_FP16:
+    if (args.asym_frac is not None or args.sparse_zeros) and kind_id != iq.KIND_FP16:
         # measured share of asymmetric groups (scale sign bit) over the quantised range of cache 0
         flag_density = {}
         for which, name in ((0, "k"), (1, "v")):
@@ -519,8 +527,8 @@ def main():
     torch.cuda.synchronize()
     other_ms = time_only(step_serial, max(1, 200 // n_layers)) if overlapped else None
 
-    per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens)
-    alg_bytes = per_unit * units
+    per_unit, units = algorithmic_bytes(w, cfg, iq, w.n_tokens, flag_density["v"] if flag_density else None)
+    alg_bytes = int(round(per_unit * units))
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
 
     # yardstick: a plain streaming read of the same number of bytes (rotating buffers, so the
@@ -577,8 +585,9 @@ def main():
                    "step_mode": args.step_mode, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
                    "v_bits": args.v_bits or w.bits,
+                   "sparse_zeros": int(args.sparse_zeros),
                    **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}
-                      if args.asym_frac is not None else {}),
+                      if flag_density is not None else {}),
                    "group": w.group, "w_sink": w.w_sink, "w_recent": w.w_recent,
                    "k_mode": ["sym", "asym", "hybrid"][w.k_mode], "v_mode": ["sym", "asym", "hybrid"][w.v_mode],
                    "layers": n_layers, "cache_instances": n_inst},

@@ -112,6 +112,12 @@ typedef struct {
   int32_t v_bits;          /* width of the value codes: 2, 3 or 4; 0 = same as bits, which is then the
                               width of both (the paper's Hybrid and Small presets pair 3-bit keys
                               with 2-bit values: Section "Experimental Setup") */
+  int32_t sparse_zeros;    /* 0 or 1; a hint for innerq_decode_attention on inner-grouped caches whose value
+                              mode is INNERQ_HYBRID, results identical either way.  0: zero-points are streamed
+                              with the codes (right when many groups are asymmetric).  1: a zero-point is read
+                              only where its group's flag is set, so 128-byte lines of zero-points that hold no
+                              asymmetric group are never fetched (Section "Sparsity of M": the paper measures
+                              about 1 % asymmetric groups and leaves exploiting that to future work). */
 } innerq_config_t;
 
 typedef struct {

@@ -30,7 +30,7 @@ class innerq_config_t(C.Structure):
                 ("head_dim", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
                 ("w_sink", C.c_int32), ("w_recent", C.c_int32), ("k_mode", C.c_int32),
                 ("v_mode", C.c_int32), ("sym_denominator", C.c_int32), ("kind", C.c_int32),
-                ("capacity_tokens", C.c_int64), ("v_bits", C.c_int32)]
+                ("capacity_tokens", C.c_int64), ("v_bits", C.c_int32), ("sparse_zeros", C.c_int32)]
 
 
 class innerq_cache_t(C.Structure):
@@ -102,9 +102,9 @@ def status_string(status: int) -> str:
 
 def make_config(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
                 k_mode=HYBRID, v_mode=HYBRID, sym_denominator=0, kind=KIND_INNER,
-                capacity_tokens=0, v_bits=0) -> innerq_config_t:
+                capacity_tokens=0, v_bits=0, sparse_zeros=0) -> innerq_config_t:
     return innerq_config_t(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
-                           k_mode, v_mode, sym_denominator, kind, capacity_tokens, v_bits)
+                           k_mode, v_mode, sym_denominator, kind, capacity_tokens, v_bits, sparse_zeros)
 
 
 def innerq_validate_config(cfg: innerq_config_t) -> int:

@@ -46,6 +46,7 @@ int check_config(const innerq_config_t* c) {
   if (c->v_bits < 0 || c->v_bits > 8) return INNERQ_E_ARG;
   if (c->v_bits != 0 && c->v_bits != 2 && c->v_bits != 3 && c->v_bits != 4) return INNERQ_E_UNSUPPORTED;
   if (c->group != 32 && c->group != 64) return INNERQ_E_UNSUPPORTED;
+  if (c->sparse_zeros != 0 && c->sparse_zeros != 1) return INNERQ_E_ARG;
   return INNERQ_OK;
 }
 
@@ -300,6 +301,7 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
   a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
   a.bits = bits_of(c, 0); a.v_bits = bits_of(c, 1); a.group = c.group; a.w_sink = c.w_sink;
   a.capacity = c.capacity_tokens; a.n_tokens = N;
+  a.sparse_zeros = c.sparse_zeros;
 
   // Tokens [w_sink, w_sink + n_both) are in the quantised store for both K and V: the split-K
   // range.  Everything else (sink window, recent windows, and the < G tokens quantised in only

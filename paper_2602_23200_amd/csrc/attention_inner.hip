@@ -132,8 +132,13 @@ struct TileRegs {
   __device__ uint32_t v_high(int gi, int ch, int w) const { return vw[gi][ch * CW + G * 2 / 32 + w]; }
 };
 
-// KB, VB: widths of the key and value codes.
-template <int KB, int VB, int G, int NH4, bool ZK, bool ZV>
+// KB, VB: widths of the key and value codes.  ZK: the key zero-point array exists (the key mode is not
+// symmetric-only).  ZV: 0 = no value zero-point array; 1 = zero-points read densely, one tile ahead with
+// everything else; 2 = sparse (Section "Sparsity of M": the flag matrix is mostly zero): a lane reads the
+// zero-points of its two channels only if one of the two groups is flagged asymmetric (the flag is the
+// sign bit of the scale it already holds), at the start of the tile that needs them, so a 128-byte line
+// of zero-points (64 channels of one token-group) that holds no asymmetric group is never fetched.
+template <int KB, int VB, int G, int NH4, bool ZK, int ZV>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles, int base_t, int rem_t,
                                                                                                  int r) {
   constexpr int LBK = KB == 3 ? 2 : KB, LBV = VB == 3 ? 2 : VB;   // field width of the (low) plane
@@ -155,7 +160,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int lane = threadIdx.x;
   const int hk = (int)blockIdx.y, b = (int)blockIdx.z;
   const long long bh = (long long)b * a.n_kv_heads + hk;
-  constexpr bool has_kz = ZK, has_vz = ZV;       // zero-point arrays exist unless the tensor is symmetric-only
+  constexpr bool has_kz = ZK, has_vz = ZV != 0;  // zero-point arrays exist unless the tensor is symmetric-only
+  constexpr bool late_vz = ZV == 2;              // value zero-points: only where flagged, at the start of their tile
 
   // ---- tile range of this wavefront.  The first win.n_chunks wavefronts of a (batch, kv-head)
   // also serve one chunk of the fp16 windows each (after their tiles) and get win_tiles tiles;
@@ -230,7 +236,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
       t.vs[gi] = stream_load(reinterpret_cast<const uint32_t*>(vscales + ch));
-      if constexpr (has_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + ch));
+      if constexpr (has_vz && !late_vz) t.vz[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + ch));
     }
   };
 
@@ -345,6 +351,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int pa_lane = (lane & 3) * TILE;
 
   auto process = [&](const Regs& cur, int tile, bool first) {
+    // sparse value zero-points: the lanes whose scale pair carries a flag fetch theirs now; they are
+    // needed at the end of the tile
+    uint32_t vz_late[GPT];
+    if constexpr (late_vz) {
+#pragma unroll
+      for (int gi = 0; gi < GPT; ++gi) {
+        int grp = tile * GPT + gi;
+        grp = grp > last_group ? last_group : grp;
+        vz_late[gi] = 0u;
+        if (cur.vs[gi] & 0x80008000u)
+          vz_late[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + (uint32_t)grp * D + 2 * lane));
+      }
+    }
     // ================= scores: lane = token (Eq. att:1 with Eq. hybrid_dequant fused) =================
     // one MFMA chain per key group, the chains interleaved so that consecutive MFMAs are independent
     float4_t acc[NG][NH4];
@@ -528,8 +547,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if constexpr (has_vz) {
         const uint32_t mpair = __builtin_bit_cast(
             uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, spair), half2_t{(_Float16)0, (_Float16)0}));
-        z0 = __builtin_fmaf((float)half_of(mpair, 0), (float)(-HALFV), (float)half_of(cur.vz[gi], 0));
-        z1 = __builtin_fmaf((float)half_of(mpair, 1), (float)(-HALFV), (float)half_of(cur.vz[gi], 1));
+        const uint32_t zpair = late_vz ? vz_late[gi] : cur.vz[gi];
+        z0 = __builtin_fmaf((float)half_of(mpair, 0), (float)(-HALFV), (float)half_of(zpair, 0));
+        z1 = __builtin_fmaf((float)half_of(mpair, 1), (float)(-HALFV), (float)half_of(zpair, 1));
       } else {
         z0 = S0 * (float)(-HALFV);
         z1 = S1 * (float)(-HALFV);
@@ -608,7 +628,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // configuration, 8 on the 8k x 32 G = 64 one, each 2 to 4 % better than the other's value).
 inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 8 : 11) * len / 64); }
 
-template <int KB, int VB, int G, bool ZK, bool ZV>
+template <int KB, int VB, int G, bool ZK, int ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // A window chunk costs its wavefront about as much time as window_cost() tiles: the wavefronts
@@ -633,7 +653,7 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
 }
 
 // Wavefronts of this kernel instance that one compute unit holds at once (a host-side query).
-template <int KB, int VB, int G, bool ZK, bool ZV>
+template <int KB, int VB, int G, bool ZK, int ZV>
 int resident_z(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   int n = 0;
@@ -643,22 +663,29 @@ int resident_z(const AttnArgs& a) {
   return (e == hipSuccess && n > 0) ? n : 8;
 }
 
+// 0: no value zero-point array; 1: read densely; 2: read only where a group is flagged
+inline int value_zero_mode(const AttnArgs& a) { return a.v.zeros == nullptr ? 0 : (a.sparse_zeros ? 2 : 1); }
+
 template <int KB, int VB, int G>
 hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
-  const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return launch_z<KB, VB, G, true, true>(a, n_both, n_splits, win, L);
-  if (zk) return launch_z<KB, VB, G, true, false>(a, n_both, n_splits, win, L);
-  if (zv) return launch_z<KB, VB, G, false, true>(a, n_both, n_splits, win, L);
-  return launch_z<KB, VB, G, false, false>(a, n_both, n_splits, win, L);
+  const bool zk = a.k.zeros != nullptr;
+  const int zv = value_zero_mode(a);
+  if (zk) {
+    if (zv == 2) return launch_z<KB, VB, G, true, 2>(a, n_both, n_splits, win, L);
+    if (zv == 1) return launch_z<KB, VB, G, true, 1>(a, n_both, n_splits, win, L);
+    return launch_z<KB, VB, G, true, 0>(a, n_both, n_splits, win, L);
+  }
+  if (zv == 2) return launch_z<KB, VB, G, false, 2>(a, n_both, n_splits, win, L);
+  if (zv == 1) return launch_z<KB, VB, G, false, 1>(a, n_both, n_splits, win, L);
+  return launch_z<KB, VB, G, false, 0>(a, n_both, n_splits, win, L);
 }
 
 template <int KB, int VB, int G>
 int resident_t(const AttnArgs& a) {
-  const bool zk = a.k.zeros != nullptr, zv = a.v.zeros != nullptr;
-  if (zk && zv) return resident_z<KB, VB, G, true, true>(a);
-  if (zk) return resident_z<KB, VB, G, true, false>(a);
-  if (zv) return resident_z<KB, VB, G, false, true>(a);
-  return resident_z<KB, VB, G, false, false>(a);
+  const bool zk = a.k.zeros != nullptr;
+  const int zv = value_zero_mode(a);
+  if (zk) return zv == 2 ? resident_z<KB, VB, G, true, 2>(a) : zv == 1 ? resident_z<KB, VB, G, true, 1>(a) : resident_z<KB, VB, G, true, 0>(a);
+  return zv == 2 ? resident_z<KB, VB, G, false, 2>(a) : zv == 1 ? resident_z<KB, VB, G, false, 1>(a) : resident_z<KB, VB, G, false, 0>(a);
 }
 
 }  // namespace
@@ -711,11 +738,11 @@ int attention_inner_waves_per_cu(const AttnArgs& a) {
   if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
     return attention_inner_f4_waves_per_cu(a);
   // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
-  static CachedInt cache[4][2][2][2][2];
+  static CachedInt cache[4][2][2][3][2];
   const int r = a.n_q_heads / a.n_kv_heads;
   const int wp = width_pair(a);
   if (wp < 0) return 8;
-  return cache[wp][a.group == 64][a.k.zeros != nullptr][a.v.zeros != nullptr][r > 4].get(
+  return cache[wp][a.group == 64][a.k.zeros != nullptr][value_zero_mode(a)][r > 4].get(
       [&] { return for_widths(a, ResidentFn{a}); });
 }
 

@@ -110,6 +110,7 @@ struct AttnArgs {
   int n_partials;           // partial slots per head in this launch
   int batch, n_q_heads, n_kv_heads, bits, v_bits, group, w_sink;   // bits: key codes, v_bits: value codes
   long long capacity, n_tokens;
+  int sparse_zeros;         // value zero-points of the fused inner kernel: read only where a group is flagged asymmetric
 };
 
 // Generic (any form, element-by-element) partial attention over the token set

@@ -45,6 +45,7 @@ def test_struct_layout_matches_header_order():
     # twelve int32, one int64, one int32 (+ tail padding to the int64 alignment)
     assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8 + 8
     assert iq.innerq_config_t.capacity_tokens.offset == 48 and iq.innerq_config_t.v_bits.offset == 56
+    assert iq.innerq_config_t.sparse_zeros.offset == 60
     assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8 + 8
     assert iq.innerq_cache_t.store_ahead_tokens.offset == 88
 

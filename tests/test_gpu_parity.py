@@ -878,3 +878,40 @@ def test_decode_step_long_context_layer_full_size_sampled(env):
     assert spills
     check_at = sorted({0, spills[0], n_steps - 1})
     _decode_steps_full_size(torch, iq, w, o, Kd, Vd, keep, n_prompt, n_steps, check_at, layer=layer, inv=inv, norm=norm)
+
+
+@pytest.mark.parametrize("frac", [0.0, 0.02, 0.5, 1.0])
+@pytest.mark.parametrize("bits,group,k_mode", [(2, 32, orc.HYBRID), (2, 64, orc.SYM), (4, 32, orc.HYBRID), (3, 32, orc.SYM)])
+def test_sparse_value_zero_points_equal_the_dense_read(env, frac, bits, group, k_mode):
+    """sparse_zeros = 1 (a value zero-point is fetched only where its group is flagged asymmetric) must give
+    the output of the dense read bit for bit, at every flag density from none to all, and stay within
+    tolerance of the oracle (Section "Sparsity of M")."""
+    torch, iq = env
+    import bench
+    from dataclasses import replace
+    w = small(n_tokens=4 + 48 + 20 * group + 7, bits=bits, group=group, k_mode=k_mode, v_mode=orc.HYBRID)
+    o = oracle_config(w)
+    B, Hk, N, d, G = w.batch, w.n_kv_heads, w.n_tokens, w.head_dim, w.group
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(23)
+    K, _ = wl.kv_full(w)
+    n_grp = (N - w.w_sink) // G
+    vg = bench.crafted_groups(torch, gen, (B, Hk, n_grp, d), G, min(bits, 4), frac)
+    v = torch.randn((B, Hk, N, d), device="cuda", generator=gen).half()
+    v[:, :, w.w_sink:w.w_sink + n_grp * G] = vg.permute(0, 1, 2, 4, 3).reshape(B, Hk, n_grp * G, d)
+    g = iq.allocate_cache(gpu_config(o))
+    iq.innerq_quantize_append(g, to_dev(torch, K), v.contiguous())
+    torch.cuda.synchronize()
+    flags = np.signbit(gpu_buffer_as_numpy(g, o, "v_scales"))[:, :, :(N - w.w_sink - w.w_recent) // G]
+    if bits != 3:                                           # (the crafted grids are exact for 2 and 4 bits)
+        assert abs(flags.mean() - frac) <= 0.05
+    q = to_dev(torch, wl.query(w))
+    ws = iq.allocate_workspace(g.cfg)
+    dense = iq.innerq_decode_attention(g, q, ws)
+    cfg_sparse = iq.make_config(o.batch, o.n_q_heads, o.n_kv_heads, o.head_dim, o.bits, o.group, o.w_sink, o.w_recent,
+                                o.k_mode, o.v_mode, o.sym_denominator, o.kind, o.capacity_tokens, o.v_bits, 1)
+    sparse = iq.innerq_decode_attention(replace(g, cfg=cfg_sparse), q, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dense, sparse)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, v.cpu().numpy()), wl.query(w))
+    assert max_rel_err(sparse.cpu().numpy(), want) <= TOL
