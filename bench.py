@@ -254,11 +254,25 @@ def prefill_rates(torch, iq, w, cfg, gen):
     iq.innerq_quantize_append(caches[0], k, v)
     t_app = timed(lambda c=iter(caches[1:]): iq.innerq_quantize_append(next(c), k, v), 2)
     written = sum(b.numel() for b in caches[1].buffers.values() if b is not None)
+    del caches
+    # the two together, the keys divided by the factors on their way in: separate calls against innerq_prefill
+    def separate(c):
+        _, inv = iq.innerq_calibrate_key_norm(cfg, k)
+        iq.innerq_quantize_append(c, k, v, k_inv_norm=inv)
+
+    n_rep = 4
+    caches = [iq.allocate_cache(cfg) for _ in range(2 * n_rep + 2)]
+    separate(caches[0])
+    iq.innerq_prefill(caches[1], k, v)
+    t_sep = timed(lambda c=iter(caches[2:2 + n_rep]): separate(next(c)), n_rep)
+    t_one = timed(lambda c=iter(caches[2 + n_rep:]): iq.innerq_prefill(next(c), k, v), n_rep)
     print(json.dumps({
         "prefill": True, "workload": w.name, "tokens": N, "batch": B,
         "calibrate_key_norm": {"ms": t_cal * 1e3, "read_GBps": fp16_bytes / t_cal / 1e9},
         "bulk_quantize_append": {"ms": t_app * 1e3, "read_GBps": 2 * fp16_bytes / t_app / 1e9,
                                  "tokens_per_s": B * N / t_app, "cache_bytes_allocated": written},
+        "calibrate_then_append_with_factors": {"ms": t_sep * 1e3, "launches": 4},
+        "innerq_prefill": {"ms": t_one * 1e3, "launches": 3, "tokens_per_s": B * N / t_one},
     }))
 
 

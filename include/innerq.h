@@ -192,6 +192,20 @@ int innerq_quantize_append(const innerq_config_t *cfg, innerq_cache_t *cache, co
                            const void *v_new, int64_t t_new, const float *k_inv_norm,
                            void *hip_stream);
 
+/* The end of prefill in one call: innerq_calibrate_key_norm over the keys of a prompt followed by
+ * innerq_quantize_append of that prompt with the keys divided by the factors on their way in
+ * (Section "Per-channel Normalization of K": the factors are computed once at the end of prefill;
+ * Eq. kv_cache_init_quantized_window).  Same arguments as those two calls; the cache must be empty
+ * (n_tokens == 0, else INNERQ_E_ARG); norm_out / inv_norm_out are written as by
+ * innerq_calibrate_key_norm and the cache contents are bit-identical to the two separate calls.
+ * What it saves: the maximum over the keys runs in the same launch as everything that does not
+ * depend on it (quantising the values, filling the value windows), so the prompt's keys are read
+ * twice and its values once in three launches instead of four, and the memory-bound maximum hides
+ * behind the arithmetic-bound value quantisation. */
+int innerq_prefill(const innerq_config_t *cfg, innerq_cache_t *cache, const void *k_fp16,
+                   const void *v_fp16, int64_t n_tokens, int per_head, float *norm_out,
+                   float *inv_norm_out, void *hip_stream);
+
 /* One decode step of attention for one new query per sequence (Eq. att:1-3
  * with Eq. kv_cached_quantized): out = softmax(q K^T / sqrt(d)) V over all
  * cache->n_tokens cached tokens, where K and V are the fp16 windows and the

@@ -70,6 +70,9 @@ def lib() -> C.CDLL:
         L.innerq_quantize_append.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_int64,
                                              C.c_void_p, C.c_void_p]
         L.innerq_quantize_append.restype = C.c_int
+        L.innerq_prefill.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
+        L.innerq_prefill.restype = C.c_int
         L.innerq_decode_attention.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.innerq_decode_attention.restype = C.c_int
@@ -196,6 +199,22 @@ def innerq_quantize_append(cache: Cache, k_new, v_new, k_inv_norm=None, stream=N
                                       k_new.shape[2], _ptr(k_inv_norm), _stream(stream))
     if st != OK:
         raise InnerQError(st, "innerq_quantize_append")
+
+
+def innerq_prefill(cache: Cache, k, v, per_head: bool = False, stream=None):
+    """Calibrate the key factors over the prompt k and append the prompt (k divided by them) to the empty cache:
+    k, v fp16 CUDA tensors [B, Hk, N, d] -> (norm, inv_norm) fp32 [Hk, d]."""
+    import torch
+    for t in (k, v):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert k.shape == v.shape
+    norm = torch.empty(cache.cfg.n_kv_heads, cache.cfg.head_dim, dtype=torch.float32, device=k.device)
+    inv = torch.empty_like(norm)
+    st = lib().innerq_prefill(C.byref(cache.cfg), C.byref(cache.c), k.data_ptr(), v.data_ptr(), k.shape[2],
+                              int(per_head), norm.data_ptr(), inv.data_ptr(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_prefill")
+    return norm, inv
 
 
 def innerq_decode_attention(cache: Cache, q, workspace, out=None, q_scale=None, stream=None):

@@ -194,17 +194,12 @@ int innerq_calibrate_key_norm(const innerq_config_t* cfg, const void* k_fp16, in
 // cache: from the rows state `from` needs to the rows state `to` needs (a state = a token count).
 // The ordinary append has from = n_tokens, to = n_tokens + t_new; the deferred forms run one
 // token ahead.
-static int quantize_impl(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,
-                         int64_t t_new, const float* k_inv_norm, long long from, long long to, void* hip_stream,
-                         const AttnArgs* merge = nullptr) {
-  if (t_new > 0 && (!k_new || !v_new)) return INNERQ_E_NULL;
-  if ((k_new && misaligned(k_new)) || (v_new && misaligned(v_new)) || (k_inv_norm && misaligned(k_inv_norm)))
-    return INNERQ_E_ALIGN;
-  const long long n0 = cache->n_tokens, n1 = n0 + t_new;
-  if (n1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
-  if (to > cfg->capacity_tokens) to = cfg->capacity_tokens;
-  if (from > to) from = to;
 
+// Kernel arguments of an append of t_new tokens that quantises the store rows between the states
+// `from` and `to` (token counts).
+static QuantArgs quant_args(const innerq_config_t* cfg, const innerq_cache_t* cache, const void* k_new,
+                            const void* v_new, int64_t t_new, const float* k_inv_norm, long long from, long long to) {
+  const long long n0 = cache->n_tokens, n1 = n0 + t_new;
   QuantArgs a;
   a.inv_norm = k_inv_norm;
   a.batch = cfg->batch; a.n_kv_heads = cfg->n_kv_heads; a.group = cfg->group;
@@ -233,6 +228,20 @@ static int quantize_impl(const innerq_config_t* cfg, innerq_cache_t* cache, cons
     j.lanes = groups >= 4096 ? 1 : 8;
     j.normalise = (w == 0 && k_inv_norm) ? 1 : 0;
   }
+  return a;
+}
+
+static int quantize_impl(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,
+                         int64_t t_new, const float* k_inv_norm, long long from, long long to, void* hip_stream,
+                         const AttnArgs* merge = nullptr) {
+  if (t_new > 0 && (!k_new || !v_new)) return INNERQ_E_NULL;
+  if ((k_new && misaligned(k_new)) || (v_new && misaligned(v_new)) || (k_inv_norm && misaligned(k_inv_norm)))
+    return INNERQ_E_ALIGN;
+  const long long n1 = cache->n_tokens + t_new;
+  if (n1 > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  if (to > cfg->capacity_tokens) to = cfg->capacity_tokens;
+  if (from > to) from = to;
+  const QuantArgs a = quant_args(cfg, cache, k_new, v_new, t_new, k_inv_norm, from, to);
   const hipError_t e = launch_quantize(a, static_cast<hipStream_t>(hip_stream), merge);
   if (e != hipSuccess) return INNERQ_E_HIP;
   cache->n_tokens = n1;
@@ -253,6 +262,25 @@ int innerq_quantize_append(const innerq_config_t* cfg, innerq_cache_t* cache, co
   if (!k_new || !v_new) return INNERQ_E_NULL;
   return quantize_impl(cfg, cache, k_new, v_new, t_new, k_inv_norm, cache->n_tokens, cache->n_tokens + t_new,
                        hip_stream);
+}
+
+int innerq_prefill(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_fp16, const void* v_fp16,
+                   int64_t n_tokens, int per_head, float* norm_out, float* inv_norm_out, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  st = check_cache(*cfg, cache);
+  if (st != INNERQ_OK) return st;
+  if (!k_fp16 || !v_fp16 || !norm_out || !inv_norm_out) return INNERQ_E_NULL;
+  if (misaligned(k_fp16) || misaligned(v_fp16) || misaligned(norm_out) || misaligned(inv_norm_out)) return INNERQ_E_ALIGN;
+  if (n_tokens < 1 || (per_head != 0 && per_head != 1) || cache->n_tokens != 0) return INNERQ_E_ARG;
+  if (n_tokens > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  const QuantArgs a = quant_args(cfg, cache, k_fp16, v_fp16, n_tokens, inv_norm_out, 0, n_tokens);
+  const hipError_t e = launch_prefill(a, static_cast<const __half*>(k_fp16), n_tokens, per_head, norm_out, inv_norm_out,
+                                      static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return INNERQ_E_HIP;
+  cache->n_tokens = n_tokens;
+  cache->store_ahead_tokens = n_tokens;
+  return INNERQ_OK;
 }
 
 int innerq_quantize_ahead(const innerq_config_t* cfg, innerq_cache_t* cache, void* hip_stream) {

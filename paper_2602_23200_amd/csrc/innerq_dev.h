@@ -97,6 +97,9 @@ struct AttnArgs;
 // merge (may be null): the log-sum-exp merge of an attention call whose partials are complete on
 // this stream rides in the same launch (or, for the rare two-launch appends, goes first).
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t stream, const AttnArgs* merge = nullptr);
+// Calibration and bulk append of one prompt into an empty cache in three launches (zero, maxima + values, keys).
+hipError_t launch_prefill(const QuantArgs& a, const __half* k, long long n_tokens, int per_head, float* norm_out,
+                          float* inv_out, hipStream_t stream);
 hipError_t launch_calibrate(const __half* k, int batch, int n_kv_heads, long long n_tokens, int per_head,
                             float* norm_out, float* inv_out, hipStream_t stream);
 

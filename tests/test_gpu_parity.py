@@ -915,3 +915,35 @@ def test_sparse_value_zero_points_equal_the_dense_read(env, frac, bits, group, k
     assert torch.equal(dense, sparse)
     want = orc.decode_attention(o, orc.cache_init_prefill(o, K, v.cpu().numpy()), wl.query(w))
     assert max_rel_err(sparse.cpu().numpy(), want) <= TOL
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("per_head,group,n_tokens", [(False, 32, 2500), (True, 64, 1300), (False, 32, 37)])
+def test_prefill_in_one_call_equals_calibration_then_append(env, kind, per_head, group, n_tokens):
+    """innerq_prefill (maxima of the keys in the launch that quantises the values, keys in a second
+    launch) against innerq_calibrate_key_norm + innerq_quantize_append: factors and every cache byte
+    identical, and both equal to the oracle's calibration and cache."""
+    torch, iq = env
+    w = small(n_tokens=n_tokens, batch=3, n_kv_heads=4, n_q_heads=8, group=group)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    K[:, 2, :, 5] = 0                                   # a dead channel -> factor 1
+    Kd, Vd = to_dev(torch, K), to_dev(torch, V)
+    g = iq.allocate_cache(gpu_config(o))
+    norm, inv = iq.innerq_prefill(g, Kd, Vd, per_head=per_head)
+    torch.cuda.synchronize()
+    want_n, want_i = orc.calibrate_key_norm(K, per_head)
+    assert np.array_equal(norm.cpu().numpy(), want_n) and np.array_equal(inv.cpu().numpy(), want_i)
+    want = orc.cache_init_prefill(o, K, V, k_inv_norm=want_i)
+    assert g.n_tokens == n_tokens
+    assert_cache_equal(g, want, o, what="prefill in one call")
+    g2 = iq.allocate_cache(gpu_config(o))
+    n2, i2 = iq.innerq_calibrate_key_norm(g2.cfg, Kd, per_head)
+    iq.innerq_quantize_append(g2, Kd, Vd, k_inv_norm=i2)
+    torch.cuda.synchronize()
+    assert torch.equal(n2, norm) and torch.equal(i2, inv)
+    for name in g.buffers:
+        if g.buffers[name] is not None:
+            assert torch.equal(g.buffers[name], g2.buffers[name]), name
+    with pytest.raises(iq.InnerQError):                 # only into an empty cache
+        iq.innerq_prefill(g, Kd, Vd, per_head=per_head)
