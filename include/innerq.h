@@ -300,6 +300,31 @@ int innerq_decode_step(const innerq_config_t *cfg, innerq_cache_t *cache, const 
                        const void *v_new, const void *q_fp16, const float *q_scale, void *out,
                        int out_is_fp32, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* innerq_decode_step for a batch whose sequences are not equally long, with the token counts in
+ * DEVICE memory (the paper's Section "Latency" leaves sequences of different lengths and the
+ * scheduling around them to future work; a step whose lengths never pass through the host can
+ * also be recorded once in a HIP graph and replayed: the library records no memset and makes no
+ * host-side decision that depends on a length).
+ *   n_tokens_dev  device, int32 [B]: tokens cached per sequence before the step.  Read by the
+ *                 kernels; the second launch adds one to every entry.  cache->n_tokens and
+ *                 cache->store_ahead_tokens (host) are neither read nor written.
+ *   max_tokens    host: a bound, n_tokens_dev[b] + 1 <= max_tokens <= capacity_tokens for every b.
+ *                 It only sizes the launch (one wavefront per split of the longest sequence
+ *                 allowed; a shorter sequence leaves some of its wavefronts without work), so a
+ *                 loose bound costs idle wavefronts, never correctness.  A count outside the bound
+ *                 is clamped on the device (that sequence's result is then unspecified; no buffer
+ *                 is overrun).
+ * Per sequence b the result equals innerq_decode_step on a cache of n_tokens_dev[b] tokens, bit for
+ * bit in the cache; every sequence's store must have been run one step ahead (innerq_quantize_ahead
+ * when it was filled, then this call keeps it so).  Inner-grouped caches on the fused kernel only
+ * (INNERQ_E_UNSUPPORTED otherwise: outer-grouped and fp16 caches, more than 8 query heads per kv
+ * head).  Other arguments and errors as innerq_decode_step. */
+int innerq_decode_step_ragged(const innerq_config_t *cfg, const innerq_cache_t *cache,
+                              int32_t *n_tokens_dev, int64_t max_tokens, const void *k_new,
+                              const void *v_new, const void *q_fp16, const float *q_scale,
+                              void *out, int out_is_fp32, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+
 /* Measurement hook (no counterpart in the paper; its Section "Latency" times the fused
  * dequantise-and-multiply kernels on their own, and this lets a benchmark do the same).
  * The next attention call made by the calling host thread (innerq_decode_attention,

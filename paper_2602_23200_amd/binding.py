@@ -87,6 +87,10 @@ def lib() -> C.CDLL:
         L.innerq_decode_step.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
         L.innerq_decode_step.restype = C.c_int
+        L.innerq_decode_step_ragged.argtypes = [cfgp, cachep, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t,
+                                                C.c_void_p]
+        L.innerq_decode_step_ragged.restype = C.c_int
         L.innerq_append_deferred.argtypes = [cfgp, cachep, C.c_void_p, C.c_void_p, C.c_void_p]
         L.innerq_append_deferred.restype = C.c_int
         L.innerq_profile_next_attention.argtypes = [C.c_void_p, C.c_void_p]
@@ -289,6 +293,43 @@ def innerq_decode_step(cache: Cache, k_new, v_new, q, workspace, out=None, q_sca
     if st != OK:
         raise InnerQError(st, "innerq_decode_step")
     return out
+
+
+def innerq_decode_step_ragged(cache: Cache, n_tokens_dev, max_tokens: int, k_new, v_new, q, workspace, out=None,
+                              q_scale=None, stream=None):
+    """innerq_decode_step with one token count per sequence in device memory (int32 CUDA tensor [B], advanced by
+    the call); max_tokens bounds every count + 1."""
+    import torch
+    for t in (k_new, v_new, q):
+        assert t.dtype == torch.float16 and t.is_contiguous() and t.is_cuda
+    assert n_tokens_dev.dtype == torch.int32 and n_tokens_dev.is_cuda and n_tokens_dev.is_contiguous()
+    assert k_new.shape == v_new.shape and k_new.shape[2] == 1
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    st = lib().innerq_decode_step_ragged(C.byref(cache.cfg), C.byref(cache.c), n_tokens_dev.data_ptr(), max_tokens,
+                                         k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(), _ptr(q_scale),
+                                         out.data_ptr(), int(out.dtype == torch.float32), workspace.data_ptr(),
+                                         workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != OK:
+        raise InnerQError(st, "innerq_decode_step_ragged")
+    return out
+
+
+def sequence_view(cache: Cache, b: int) -> Cache:
+    """Sequence b of a batched cache as a cache of its own (batch 1) over the same device memory: every buffer
+    is laid out [B][...], so a sequence is one contiguous slice of each."""
+    from dataclasses import replace as _replace
+    cfg = innerq_config_t.from_buffer_copy(bytes(cache.cfg))
+    B = cfg.batch
+    cfg.batch = 1
+    bufs, c = {}, innerq_cache_t()
+    for name in BUFFER_NAMES:
+        t = cache.buffers[name]
+        bufs[name] = None if t is None else t.view(B, -1)[b]
+        setattr(c, name, _ptr(bufs[name]))
+    c.n_tokens = 0
+    c.store_ahead_tokens = 0
+    return Cache(cfg, bufs, c)
 
 
 def innerq_append_deferred(cache: Cache, k_new, v_new, stream=None) -> None:

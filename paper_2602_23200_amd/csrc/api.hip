@@ -28,6 +28,10 @@ inline int split_cap(const innerq_config_t& c) {
   return (int)s;
 }
 
+// Bytes at the start of the workspace for one int per sequence: the fused kernel of a ragged step leaves
+// the sequences' token counts there for the append that follows it.
+inline size_t seq_bytes(const innerq_config_t& c) { return (((size_t)c.batch * sizeof(int) + 255) / 256) * 256; }
+
 int check_config(const innerq_config_t* c) {
   if (!c) return INNERQ_E_NULL;
   if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return INNERQ_E_ARG;
@@ -161,7 +165,7 @@ size_t innerq_workspace_bytes(const innerq_config_t* cfg) {
   if (check_config(cfg) != INNERQ_OK) return 0;
   const size_t heads = (size_t)cfg->batch * cfg->n_q_heads;
   const size_t partials = (size_t)split_cap(*cfg) + window_chunk_cap(*cfg);
-  return heads * partials * (kHeadDim + 2) * sizeof(float) + 64;
+  return seq_bytes(*cfg) + heads * partials * (kHeadDim + 2) * sizeof(float) + 64;
 }
 
 int innerq_partition(const innerq_config_t* cfg, int which, int64_t n_tokens, int64_t* n_sink,
@@ -205,8 +209,10 @@ static QuantArgs quant_args(const innerq_config_t* cfg, const innerq_cache_t* ca
   a.batch = cfg->batch; a.n_kv_heads = cfg->n_kv_heads; a.group = cfg->group;
   a.w_sink = cfg->w_sink; a.sym_den_literal = cfg->sym_denominator;
   a.capacity = cfg->capacity_tokens; a.n_old = n0; a.t_new = t_new;
+  a.w_recent = cfg->w_recent; a.n_dev = nullptr; a.n_dev_out = nullptr;
   for (int w = 0; w < 2; ++w) {
     QuantTensorJob& j = a.job[w];
+    j.is_keys = w == 0;
     j.codes = static_cast<uint8_t*>(w == 0 ? cache->k_codes : cache->v_codes);
     j.scales = static_cast<__half*>(w == 0 ? cache->k_scales : cache->v_scales);
     j.zeros = uses_zeros(*cfg, w) ? static_cast<__half*>(w == 0 ? cache->k_zeros : cache->v_zeros) : nullptr;
@@ -306,10 +312,12 @@ int innerq_append_deferred(const innerq_config_t* cfg, innerq_cache_t* cache, co
 // Attention over the first N tokens of the cache.  k_newest / v_newest (both or neither): fp16 rows
 // [B][Hk][d] of token N - 1 when that token has not been copied into its window yet.
 // defer_merge (may be null): the final merge is not launched; its arguments are returned instead.
+// n_dev (may be null): per-sequence token counts on the device (the count before this step); N is then
+// only the bound the launch is planned for.
 static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cache, long long N,
                           const void* k_newest, const void* v_newest, const void* q_fp16, const float* q_scale,
                           void* out, int out_is_fp32, void* workspace, size_t workspace_bytes, void* hip_stream,
-                          AttnArgs* defer_merge = nullptr) {
+                          AttnArgs* defer_merge = nullptr, const int* n_dev = nullptr) {
   if (!q_fp16 || !out || !workspace) return INNERQ_E_NULL;
   if (misaligned(q_fp16) || misaligned(out) || misaligned(workspace) || (q_scale && misaligned(q_scale)))
     return INNERQ_E_ALIGN;
@@ -330,14 +338,24 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
   a.bits = bits_of(c, 0); a.v_bits = bits_of(c, 1); a.group = c.group; a.w_sink = c.w_sink;
   a.capacity = c.capacity_tokens; a.n_tokens = N;
   a.sparse_zeros = c.sparse_zeros;
+  a.n_dev = n_dev;
+  a.n_copy = n_dev ? static_cast<int*>(workspace) : nullptr;
 
   // Tokens [w_sink, w_sink + n_both) are in the quantised store for both K and V: the split-K
   // range.  Everything else (sink window, recent windows, and the < G tokens quantised in only
   // one of the two tensors) goes through the generic window pass.
-  const long long n_both = a.k.n_quant < a.v.n_quant ? a.k.n_quant : a.v.n_quant;
+  long long n_both = a.k.n_quant < a.v.n_quant ? a.k.n_quant : a.v.n_quant;
   const long long n_sink = a.k.n_sink;
   const long long win_b0 = c.w_sink + n_both, win_b1 = N > win_b0 ? N : win_b0;
-  const long long win_tokens = n_sink + (win_b1 - win_b0);
+  long long win_tokens = n_sink + (win_b1 - win_b0);
+  if (n_dev) {
+    // planned for any length up to N: at least one tile's worth of wavefronts, and window chunks for the
+    // largest window set a sequence can have (sink + recent + a value group in waiting)
+    if (!attention_inner_supported(a)) return INNERQ_E_UNSUPPORTED;
+    if (n_both < 64) n_both = 64;
+    const long long most = (long long)c.w_sink + c.w_recent + c.group;
+    win_tokens = N < most ? N : most;
+  }
   const int r = c.n_q_heads / c.n_kv_heads;
   int n_splits = 0, win_chunk_len = kWindowChunk;
   // which fused kernel serves this cache (0 = none: element-by-element fallback)
@@ -389,8 +407,9 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
   if (n_win > window_chunk_cap(c)) return INNERQ_E_ARG;
   a.n_partials = n_splits + n_win;
   const size_t heads = (size_t)c.batch * c.n_q_heads;
-  if (heads * (size_t)a.n_partials * (kHeadDim + 2) * sizeof(float) + 64 > workspace_bytes) return INNERQ_E_WORKSPACE;
-  a.ws_ml = static_cast<float*>(workspace);
+  if (seq_bytes(c) + heads * (size_t)a.n_partials * (kHeadDim + 2) * sizeof(float) + 64 > workspace_bytes)
+    return INNERQ_E_WORKSPACE;
+  a.ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + seq_bytes(c));
   a.ws_o = a.ws_ml + ((heads * a.n_partials * 2 + 3) / 4) * 4;
 
   hipError_t e = hipSuccess;
@@ -488,6 +507,42 @@ int innerq_decode_attention_next(const innerq_config_t* cfg, const innerq_cache_
   if (cache->store_ahead_tokens != cache->n_tokens + 1) return INNERQ_E_ARG;   // the store was not run one step ahead
   return attention_impl(cfg, cache, cache->n_tokens + 1, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
                         workspace_bytes, hip_stream);
+}
+
+int innerq_decode_step_ragged(const innerq_config_t* cfg, const innerq_cache_t* cache, int32_t* n_tokens_dev,
+                              int64_t max_tokens, const void* k_new, const void* v_new, const void* q_fp16,
+                              const float* q_scale, void* out, int out_is_fp32, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != INNERQ_OK) return st;
+  innerq_cache_t view = cache ? *cache : innerq_cache_t{};
+  view.n_tokens = 0;                                    // (the host counter is not used on this path)
+  st = check_cache(*cfg, cache ? &view : nullptr);
+  if (st != INNERQ_OK) return st;
+  if (!k_new || !v_new || !n_tokens_dev) return INNERQ_E_NULL;
+  if (misaligned(k_new) || misaligned(v_new) || (reinterpret_cast<uintptr_t>(n_tokens_dev) & 3u)) return INNERQ_E_ALIGN;
+  if (cfg->kind != INNERQ_KIND_INNER) return INNERQ_E_UNSUPPORTED;
+  if (max_tokens < 1) return INNERQ_E_ARG;
+  if (max_tokens > cfg->capacity_tokens) return INNERQ_E_CAPACITY;
+  AttnArgs merge;
+  st = attention_impl(cfg, &view, max_tokens, k_new, v_new, q_fp16, q_scale, out, out_is_fp32, workspace,
+                      workspace_bytes, hip_stream, &merge, n_tokens_dev);
+  if (st != INNERQ_OK) return st;
+  // second launch: merge + the deferred single-token append of every sequence, each from its own count
+  // (read from the copy the fused kernel left in the workspace; the caller's counters are advanced here).
+  // The plan is the most any sequence needs: one key row, one value group, one window copy.
+  QuantArgs a = quant_args(cfg, &view, k_new, v_new, 1, nullptr, 0, 0);
+  a.n_old = 0;
+  a.n_dev = merge.n_copy;
+  a.n_dev_out = n_tokens_dev;
+  for (int w = 0; w < 2; ++w) {
+    QuantTensorJob& j = a.job[w];
+    j.row_begin = 0;
+    j.row_end = j.form == kPerChannel ? cfg->group : 1;
+    j.ring_from = 0;
+    j.lanes = 8;
+  }
+  return launch_quantize(a, static_cast<hipStream_t>(hip_stream), &merge) == hipSuccess ? INNERQ_OK : INNERQ_E_HIP;
 }
 
 int innerq_decode_step(const innerq_config_t* cfg, innerq_cache_t* cache, const void* k_new, const void* v_new,

@@ -132,6 +132,13 @@ struct TileRegs {
   __device__ uint32_t v_high(int gi, int ch, int w) const { return vw[gi][ch * CW + G * 2 / 32 + w]; }
 };
 
+// Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it.  The
+// chunk runs at the lowest issue priority next to a partner that is busy about three quarters of
+// the time, so its wall time is several times its own instruction count; the slope is the one that
+// balances the launch best when swept (8 to 11 per 64 tokens: 11 on the 32k-token G = 32
+// configuration, 8 on the 8k x 32 G = 64 one, each 2 to 4 % better than the other's value).
+__host__ __device__ inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 8 : 11) * len / 64); }
+
 // KB, VB: widths of the key and value codes.  ZK: the key zero-point array exists (the key mode is not
 // symmetric-only).  ZV: 0 = no value zero-point array; 1 = zero-points read densely, one tile ahead with
 // everything else; 2 = sparse (Section "Sparsity of M": the flag matrix is mostly zero): a lane reads the
@@ -139,8 +146,8 @@ struct TileRegs {
 // sign bit of the scale it already holds), at the start of the tile that needs them, so a 128-byte line
 // of zero-points (64 channels of one token-group) that holds no asymmetric group is never fetched.
 template <int KB, int VB, int G, int NH4, bool ZK, int ZV>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win, int win_tiles, int base_t, int rem_t,
-                                                                                                 int r) {
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) attention_inner_kernel(AttnArgs a_in, int n_both_in, int n_splits, WindowSet win_in, int win_tiles_in, int base_t_in,
+                                                                                                 int rem_t_in, int r) {
   constexpr int LBK = KB == 3 ? 2 : KB, LBV = VB == 3 ? 2 : VB;   // field width of the (low) plane
   constexpr bool HIK = KB == 3, HIV = VB == 3;                     // a plane of high bits follows it
   using FK = Fields<LBK>;
@@ -159,6 +166,40 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // host passes the quotients (heads per kv head; tiles per plain wavefront and their remainder).
   const int lane = threadIdx.x;
   const int hk = (int)blockIdx.y, b = (int)blockIdx.z;
+  // The host's plan holds for every sequence -- unless the token counts live on the device
+  // (a.n_dev: one count per sequence, the tokens cached BEFORE this step; attention runs over them
+  // plus the new token).  Then the launch shape (wavefronts, window chunks, partial slots) is the
+  // host's, planned for the longest sequence allowed, and everything that depends on the length is
+  // recomputed here for this wavefront's sequence: the partition of Eq. kv_cache_init_quantized_window,
+  // the window set and the split of the tiles over the wavefronts.  Wavefronts left without a tile
+  // write an empty partial.
+  AttnArgs a = a_in;
+  int n_both = n_both_in, win_tiles = win_tiles_in, base_t = base_t_in, rem_t = rem_t_in;
+  WindowSet win = win_in;
+  if (a_in.n_dev) {
+    long long N = (long long)a_in.n_dev[b] + 1;
+    N = N < 1 ? 1 : (N > a.capacity ? a.capacity : N);
+    if (a.n_copy && blockIdx.x == 0 && hk == 0 && lane == 0) a.n_copy[b] = (int)(N - 1);   // for the append that follows
+    const int w_recent = a.k.slots - 1;                  // (the per-token key ring has w_recent + 1 slots)
+    const long long kq = quantised_rows(a.w_sink, w_recent, a.group, kPerToken, N);
+    const long long vq = quantised_rows(a.w_sink, w_recent, a.group, kPerChannel, N);
+    const int n_sink = (int)(N < a.w_sink ? N : a.w_sink);
+    a.n_tokens = N;
+    a.k.n_sink = n_sink; a.v.n_sink = n_sink;
+    a.k.n_quant = kq; a.v.n_quant = vq;
+    n_both = (int)vq;
+    win.na = n_sink;
+    win.b0 = a.w_sink + vq;
+    win.nb = N > win.b0 ? N - win.b0 : 0;
+    const int tiles = (n_both + TILE - 1) / TILE;
+    const int cost = win.n_chunks > 0 ? window_cost((win.na + win.nb + win.n_chunks - 1) / win.n_chunks, G) : 0;
+    const int quota = (tiles + win.n_chunks * cost + n_splits - 1) / n_splits;
+    win_tiles = quota > cost ? quota - cost : 0;
+    if (win.n_chunks > 0 && win_tiles > tiles / win.n_chunks) win_tiles = tiles / win.n_chunks;
+    const int rest = tiles - win.n_chunks * win_tiles, others = n_splits - win.n_chunks;
+    base_t = rest / others;
+    rem_t = rest % others;
+  }
   const long long bh = (long long)b * a.n_kv_heads + hk;
   constexpr bool has_kz = ZK, has_vz = ZV != 0;  // zero-point arrays exist unless the tensor is symmetric-only
   constexpr bool late_vz = ZV == 2;              // value zero-points: only where flagged, at the start of their tile
@@ -621,13 +662,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
-// Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it.  The
-// chunk runs at the lowest issue priority next to a partner that is busy about three quarters of
-// the time, so its wall time is several times its own instruction count; the slope is the one that
-// balances the launch best when swept (8 to 11 per 64 tokens: 11 on the 32k-token G = 32
-// configuration, 8 on the 8k x 32 G = 64 one, each 2 to 4 % better than the other's value).
-inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 8 : 11) * len / 64); }
-
 template <int KB, int VB, int G, bool ZK, int ZV>
 hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet& win, const Launch& L) {
   const int r = a.n_q_heads / a.n_kv_heads;
@@ -643,12 +677,24 @@ hipError_t launch_z(const AttnArgs& a, int n_both, int n_splits, const WindowSet
   const int rest = n_tiles - win.n_chunks * win_tiles, others = n_splits - win.n_chunks;
   const int base_t = rest / others, rem_t = rest % others;
   dim3 grid((unsigned)n_splits, (unsigned)a.n_kv_heads, (unsigned)a.batch);
-  if (r <= 4)
-    hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
-                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
-  else
-    hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
-                          L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
+  // (the launch with dispatch events only when events were asked for: the plain launch is the one a
+  // stream capture is sure to record)
+  const bool timed = L.ev_start || L.ev_stop;
+  if (r <= 4) {
+    if (timed)
+      hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                            L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
+    else
+      hipLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 1, ZK, ZV>), grid, dim3(64), 0, L.stream, a, n_both,
+                         n_splits, win, win_tiles, base_t, rem_t, r);
+  } else {
+    if (timed)
+      hipExtLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, L.ev_start,
+                            L.ev_stop, 0, a, n_both, n_splits, win, win_tiles, base_t, rem_t, r);
+    else
+      hipLaunchKernelGGL((attention_inner_kernel<KB, VB, G, 2, ZK, ZV>), grid, dim3(64), 0, L.stream, a, n_both,
+                         n_splits, win, win_tiles, base_t, rem_t, r);
+  }
   return hipGetLastError();
 }
 
@@ -735,7 +781,7 @@ struct LaunchFn {
 std::atomic<int> g_inner_variant{0};
 
 int attention_inner_waves_per_cu(const AttnArgs& a) {
-  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a) && !a.n_dev)
     return attention_inner_f4_waves_per_cu(a);
   // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
   static CachedInt cache[4][2][2][3][2];
@@ -749,7 +795,7 @@ int attention_inner_waves_per_cu(const AttnArgs& a) {
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!attention_inner_supported(a)) return hipErrorInvalidValue;
-  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a) && !a.n_dev)
     return launch_attention_inner_f4(a, n_both_ll, n_splits, win, stream, ev_start, ev_stop);
   const Launch L = {stream, ev_start, ev_stop};
   return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});

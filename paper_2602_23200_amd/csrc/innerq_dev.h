@@ -56,6 +56,14 @@ struct Partition { long long n_sink, n_quant, n_recent; };
 
 inline int bits_of(const innerq_config_t& c, int which) { return (which == 1 && c.v_bits) ? c.v_bits : c.bits; }
 
+// Rows of a tensor's quantised store when n tokens are cached (the arithmetic of partition_of, for device code too).
+__host__ __device__ inline long long quantised_rows(int w_sink, int w_recent, int group, int form, long long n) {
+  long long mid = n - w_sink - w_recent;
+  if (mid < 0) mid = 0;
+  if (form == kPerChannel) mid -= mid % group;
+  return mid;
+}
+
 inline Partition partition_of(const innerq_config_t& c, int which, long long n) {
   Partition p;
   p.n_sink = n < c.w_sink ? n : c.w_sink;
@@ -84,6 +92,7 @@ struct QuantTensorJob {
   long long row_begin, row_end;   // store rows to quantise in this call (token = w_sink + row)
   long long ring_from;            // new tokens with index >= ring_from go to the ring
   int normalise;                  // apply k_inv_norm to tokens taken from x_new
+  int is_keys;                    // tensor 0 of the cache
 };
 
 struct QuantArgs {
@@ -91,6 +100,11 @@ struct QuantArgs {
   const float* inv_norm;          // [Hk][d] or null
   int batch, n_kv_heads, group, w_sink, sym_den_literal;
   long long capacity, n_old, t_new;
+  // per-sequence token counts (device, [B], the count before the step), or null: a.n_old holds for all;
+  // n_dev_out: the caller's counters, advanced by one per sequence by the append
+  int w_recent;
+  const int* n_dev;
+  int* n_dev_out;
 };
 
 struct AttnArgs;
@@ -114,6 +128,10 @@ struct AttnArgs {
   int batch, n_q_heads, n_kv_heads, bits, v_bits, group, w_sink;   // bits: key codes, v_bits: value codes
   long long capacity, n_tokens;
   int sparse_zeros;         // value zero-points of the fused inner kernel: read only where a group is flagged asymmetric
+  // per-sequence token counts (device, [B], the count before this step) or null; n_copy: where the fused
+  // kernel leaves a copy of them for the append that follows in the same step (workspace, [B])
+  const int* n_dev;
+  int* n_copy;
 };
 
 // Generic (any form, element-by-element) partial attention over the token set

@@ -229,22 +229,44 @@ __device__ __forceinline__ uint32_t mod32(long long n, long long d) { return (ui
 
 // Where the fp16 row of token t (absolute index) of sequence-head bh lives when the quantiser
 // wants it: still in the recent ring if it was appended by an earlier call, else in x_new.
-__device__ __forceinline__ const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long bh,
-                                          long long t, bool& from_new) {
-  from_new = t >= a.n_old;
-  if (from_new) return j.x_new + ((bh * a.t_new) + (t - a.n_old)) * kHeadDim;
+// (n_old: tokens cached before this call: a.n_old, or the sequence's own count.)
+__device__ __forceinline__ const __half* token_row(const QuantTensorJob& j, const QuantArgs& a, long long n_old,
+                                          long long bh, long long t, bool& from_new) {
+  from_new = t >= n_old;
+  if (from_new) return j.x_new + ((bh * a.t_new) + (t - n_old)) * kHeadDim;
   return j.ring + (bh * j.slots + mod32(t, j.slots)) * kHeadDim;
+}
+
+// Per-sequence token counts (a.n_dev: device memory, the count of every sequence before the step; Section
+// "Latency", closing remark: sequences of a batch need not be equally long).  The launch is planned for
+// the most any sequence can need (one key row, one value group, one window copy per sequence and head);
+// each thread then takes its own sequence's state: the deferred single-token append of a cache of n0
+// tokens copies token n0 into its window and quantises the rows between the states n0 + 1 and n0 + 2.
+// Returns false when this sequence has nothing to quantise in this step (or is full).
+__device__ __forceinline__ bool sequence_rows(const QuantArgs& a, const QuantTensorJob& j, long long bh,
+                                              long long& n_old, long long& row_begin) {
+  const long long n0 = a.n_dev[div32(bh, a.n_kv_heads)];
+  if (n0 < 0 || n0 + 1 > a.capacity) return false;
+  const long long to = n0 + 2 > a.capacity ? a.capacity : n0 + 2;
+  const long long rb = quantised_rows(a.w_sink, a.w_recent, a.group, j.form, n0 + 1);
+  const long long re = quantised_rows(a.w_sink, a.w_recent, a.group, j.form, to);
+  n_old = n0;
+  row_begin = rb;
+  return re > rb;
 }
 
 // Which of the t_new new tokens (index i, absolute token n_old + i) go to a window: i < n_a to
 // the sink, i >= i_b to the recent ring; the ones between were quantised by this same call.
 struct CopySpan { long long n_a, i_b; };
-__host__ __device__ inline CopySpan copy_span(const QuantArgs& a, const QuantTensorJob& j) {
-  long long n_a = a.w_sink - a.n_old;
+__host__ __device__ inline CopySpan copy_span(const QuantArgs& a, long long n_old, long long ring_from) {
+  long long n_a = a.w_sink - n_old;
   n_a = n_a < 0 ? 0 : (n_a > a.t_new ? a.t_new : n_a);
-  long long i_b = j.ring_from - a.n_old;
+  long long i_b = ring_from - n_old;
   i_b = i_b < n_a ? n_a : (i_b > a.t_new ? a.t_new : i_b);
   return {n_a, i_b};
+}
+__host__ __device__ inline CopySpan copy_span(const QuantArgs& a, const QuantTensorJob& j) {
+  return copy_span(a, a.n_old, j.ring_from);
 }
 
 // New tokens join the fp16 windows: the sink window while it has room, otherwise the recent
@@ -253,14 +275,24 @@ __device__ __forceinline__ void window_copy(const QuantArgs& a, const QuantTenso
   constexpr int CPR = kHeadDim / 8;
   const long long BH = (long long)a.batch * a.n_kv_heads;
   // only the new tokens that stay in a window are visited: the first n_a (sink) and those from i_b on (ring)
-  const CopySpan sp = copy_span(a, j);
+  CopySpan sp = copy_span(a, j);
   const long long n_cp = sp.n_a + (a.t_new - sp.i_b);
   if (idx >= BH * n_cp * CPR) return;
   const int ch = (int)(idx % CPR);
   const long long bh = div32(idx / CPR, n_cp);
   const long long k = idx / CPR - bh * n_cp;
+  long long n_old = a.n_old;
+  if (a.n_dev) {
+    // per-sequence count: the one new token of this sequence (the plan has n_cp = 1 for every sequence)
+    const uint32_t b = div32(bh, a.n_kv_heads);
+    n_old = a.n_dev[b];
+    if (n_old < 0 || n_old + 1 > a.capacity) return;
+    sp = copy_span(a, n_old, a.w_sink + quantised_rows(a.w_sink, a.w_recent, a.group, j.form, n_old + 1));
+    // the caller's counter of this sequence moves on: one thread per sequence (a.n_dev is a copy of it)
+    if (a.n_dev_out && j.is_keys && ch == 0 && mod32(bh, a.n_kv_heads) == 0) a.n_dev_out[b] = (int)(n_old + 1);
+  }
   const long long i = k < sp.n_a ? k : sp.i_b + (k - sp.n_a);
-  const long long t = a.n_old + i;
+  const long long t = n_old + i;
   __half* dst;
   if (t < a.w_sink) dst = j.sink + (bh * a.w_sink + t) * kHeadDim;
   else dst = j.ring + (bh * j.slots + mod32(t, j.slots)) * kHeadDim;
@@ -297,6 +329,7 @@ __device__ __forceinline__ QuantTensorJob pick_job(const QuantArgs& a, int y) {
   j.row_end = y ? v.row_end : k.row_end;
   j.ring_from = y ? v.ring_from : k.ring_from;
   j.normalise = y ? v.normalise : k.normalise;
+  j.is_keys = y ? 0 : 1;
   return j;
 }
 
@@ -320,9 +353,11 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     if (idx >= BH * n_rows * GPR) return;
     const int g = (int)(idx % GPR);
     const long long bh = div32(idx / GPR, n_rows);
-    const long long row = j.row_begin + (idx / GPR - bh * n_rows);
+    long long n_old = a.n_old, row_begin = j.row_begin;
+    if (a.n_dev && !sequence_rows(a, j, bh, n_old, row_begin)) return;
+    const long long row = row_begin + (idx / GPR - bh * n_rows);
     bool from_new;
-    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G;
+    const __half* src = token_row(j, a, n_old, bh, a.w_sink + row, from_new) + g * G;
     const bool norm = from_new && j.normalise;
     const float* inv = a.inv_norm + mod32(bh, a.n_kv_heads) * kHeadDim + g * G;
     uint32_t words[W];
@@ -383,9 +418,11 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     const long long gi = idx / 8;
     const int g = (int)(gi % GPR);
     const long long bh = div32(gi / GPR, n_rows);
-    const long long row = j.row_begin + (gi / GPR - bh * n_rows);
+    long long n_old = a.n_old, row_begin = j.row_begin;
+    if (a.n_dev && !sequence_rows(a, j, bh, n_old, row_begin)) return;
+    const long long row = row_begin + (gi / GPR - bh * n_rows);
     bool from_new;
-    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + g * G + sub * E;
+    const __half* src = token_row(j, a, n_old, bh, a.w_sink + row, from_new) + g * G + sub * E;
     float x[E];
     if constexpr (E == 4) {
       const uint2 raw = *reinterpret_cast<const uint2*>(src);
@@ -423,7 +460,9 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     if (idx >= BH * n_groups * kHeadDim) return;
     const int c = (int)(idx % kHeadDim);
     const long long bh = div32(idx / kHeadDim, n_groups);
-    const long long tg = j.row_begin / G + (idx / kHeadDim - bh * n_groups);   // token-group index in the store
+    long long n_old = a.n_old, row_begin = j.row_begin;
+    if (a.n_dev && !sequence_rows(a, j, bh, n_old, row_begin)) return;
+    const long long tg = row_begin / G + (idx / kHeadDim - bh * n_groups);   // token-group index in the store
     const float inv = j.normalise ? a.inv_norm[mod32(bh, a.n_kv_heads) * kHeadDim + c] : 1.f;
     uint32_t words[W];
     __half s, z;
@@ -445,9 +484,9 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
       }
     };
     const long long t0 = a.w_sink + tg * G;              // first token of the group
-    if (t0 >= a.n_old) {
+    if (t0 >= n_old) {
       // the whole group comes from x_new (bulk calls): one base address, a fixed stride
-      const __half* src0 = j.x_new + ((bh * a.t_new) + (t0 - a.n_old)) * kHeadDim + c;
+      const __half* src0 = j.x_new + ((bh * a.t_new) + (t0 - n_old)) * kHeadDim + c;
       run([&](int i) -> __half {
         __half v = src0[i * kHeadDim];
         if (j.normalise) v = scaled_half(h2f(v), inv);
@@ -456,7 +495,7 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     } else {
       run([&](int i) -> __half {
         bool from_new;
-        const __half* src = token_row(j, a, bh, t0 + i, from_new);
+        const __half* src = token_row(j, a, n_old, bh, t0 + i, from_new);
         __half v = src[c];
         if (from_new && j.normalise) v = scaled_half(h2f(v), inv);
         return v;
@@ -474,9 +513,11 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     if (idx >= BH * n_rows * CPR) return;
     const int ch = (int)(idx % CPR);
     const long long bh = div32(idx / CPR, n_rows);
-    const long long row = j.row_begin + (idx / CPR - bh * n_rows);
+    long long n_old = a.n_old, row_begin = j.row_begin;
+    if (a.n_dev && !sequence_rows(a, j, bh, n_old, row_begin)) return;
+    const long long row = row_begin + (idx / CPR - bh * n_rows);
     bool from_new;
-    const __half* src = token_row(j, a, bh, a.w_sink + row, from_new) + ch * 8;
+    const __half* src = token_row(j, a, n_old, bh, a.w_sink + row, from_new) + ch * 8;
     uint4 raw = *reinterpret_cast<const uint4*>(src);
     if (from_new && j.normalise) {
       __half* h = reinterpret_cast<__half*>(&raw);

@@ -54,14 +54,14 @@ def gpu_buffer_as_numpy(gcache, o: orc.Config, name: str):
     return raw.view(np.float16).reshape(B, H, o.ring_slots(which), d)
 
 
-def assert_cache_equal(gcache, ocache, o: orc.Config, bsel=slice(None), hsel=slice(None), what=""):
+def assert_cache_equal(gcache, ocache, o: orc.Config, bsel=slice(None), hsel=slice(None), what="", per_sequence=False):
     """Bit-exact comparison of every live part of the GPU cache against the oracle cache.
 
     bsel / hsel select the (batch, kv-head) slab of the GPU buffers that the oracle cache
     (possibly built for a single slab) corresponds to.
     """
     N = ocache.n_tokens
-    assert gcache.n_tokens == N
+    assert per_sequence or gcache.n_tokens == N            # (per_sequence: the counts live on the device)
     for x in "kv":
         n_s, n_q, n_r = orc.partition(o, x, N)
         form = o.form(x)

@@ -947,3 +947,104 @@ def test_prefill_in_one_call_equals_calibration_then_append(env, kind, per_head,
             assert torch.equal(g.buffers[name], g2.buffers[name]), name
     with pytest.raises(iq.InnerQError):                 # only into an empty cache
         iq.innerq_prefill(g, Kd, Vd, per_head=per_head)
+
+
+@pytest.mark.parametrize("group,lengths", [(32, [40, 700, 1900]), (64, [133, 5, 1210, 2047])])
+def test_decode_step_with_per_sequence_lengths_on_the_device(env, group, lengths):
+    """innerq_decode_step_ragged: sequences of different lengths in one batch, their token counts in device
+    memory only.  Every sequence is filled on its own (a batch-1 view of its slice of the buffers), then
+    70 steps run on the whole batch; the oracle follows each sequence separately: outputs in tolerance on
+    sampled steps, counters advanced by the device, every sequence's cache bit-exact at the end."""
+    torch, iq = env
+    n_steps = 70
+    B = len(lengths)
+    w = small(batch=B, n_kv_heads=2, n_q_heads=8, group=group, n_tokens=max(lengths) + n_steps)
+    o = oracle_config(w)
+    o1 = oracle_config(w.with_(batch=1), capacity=o.capacity_tokens)
+    K, V = wl.kv_full(w)
+    g = iq.allocate_cache(gpu_config(o))
+    want = []
+    for b, n in enumerate(lengths):
+        view = iq.sequence_view(g, b)
+        iq.innerq_quantize_append(view, to_dev(torch, K[b:b + 1, :, :n]), to_dev(torch, V[b:b + 1, :, :n]))
+        iq.innerq_quantize_ahead(view)
+        want.append(orc.cache_init_prefill(o1, K[b:b + 1, :, :n], V[b:b + 1, :, :n]))
+    n_dev = torch.tensor(lengths, dtype=torch.int32, device="cuda")
+    ws = iq.allocate_workspace(g.cfg)
+    rng = np.random.default_rng(5)
+    for i in range(n_steps):
+        # the new token of sequence b is its own next token
+        k1 = np.stack([K[b, :, n + i:n + i + 1] for b, n in enumerate(lengths)])
+        v1 = np.stack([V[b, :, n + i:n + i + 1] for b, n in enumerate(lengths)])
+        q = rng.standard_normal((B, w.n_q_heads, w.head_dim)).astype(np.float16)
+        out = iq.innerq_decode_step_ragged(g, n_dev, max(lengths) + n_steps, to_dev(torch, k1), to_dev(torch, v1),
+                                           to_dev(torch, q), ws)
+        for b in range(B):
+            orc.quantize_append(o1, want[b], k1[b:b + 1], v1[b:b + 1])
+        if i % 9 == 0 or i == n_steps - 1:
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert n_dev.cpu().tolist() == [n + i + 1 for n in lengths]
+            for b in range(B):
+                ref = orc.decode_attention(o1, want[b], q[b:b + 1])
+                assert max_rel_err(got[b:b + 1], ref) <= TOL, f"step {i} sequence {b}"
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert_cache_equal(g, want[b], o1, bsel=slice(b, b + 1), what=f"sequence {b}", per_sequence=True)
+
+
+def test_ragged_decode_step_replayed_from_a_hip_graph(env):
+    """One innerq_decode_step_ragged recorded in a HIP graph (two kernel nodes, no memset, no length on the
+    host) and replayed for successive tokens, with eager work and synchronisations between the replays:
+    every replay equals the eager call on a twin cache bit for bit, and the device counters advance."""
+    torch, iq = env
+    lengths, n_steps = [300, 77, 1500], 40
+    B = len(lengths)
+    w = small(batch=B, n_kv_heads=2, n_q_heads=8, n_tokens=max(lengths) + n_steps + 1)
+    o = oracle_config(w)
+    K, V = wl.kv_full(w)
+    caches, counters = [], []
+    for _ in range(2):                                       # twin caches: one driven by the graph, one eagerly
+        g = iq.allocate_cache(gpu_config(o))
+        for b, n in enumerate(lengths):
+            view = iq.sequence_view(g, b)
+            iq.innerq_quantize_append(view, to_dev(torch, K[b:b + 1, :, :n]), to_dev(torch, V[b:b + 1, :, :n]))
+            iq.innerq_quantize_ahead(view)
+        caches.append(g)
+        counters.append(torch.tensor(lengths, dtype=torch.int32, device="cuda"))
+    ws = [iq.allocate_workspace(caches[0].cfg) for _ in range(2)]
+    k_in = torch.zeros((B, w.n_kv_heads, 1, w.head_dim), dtype=torch.float16, device="cuda")
+    v_in, q_in = torch.zeros_like(k_in), torch.zeros((B, w.n_q_heads, w.head_dim), dtype=torch.float16, device="cuda")
+    out_graph = torch.zeros((B, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    bound = max(lengths) + n_steps + 1
+    rng = np.random.default_rng(9)
+
+    def inputs(i):
+        k1 = np.stack([K[b, :, n + i:n + i + 1] for b, n in enumerate(lengths)])
+        v1 = np.stack([V[b, :, n + i:n + i + 1] for b, n in enumerate(lengths)])
+        return to_dev(torch, k1), to_dev(torch, v1), to_dev(torch, rng.standard_normal(q_in.shape).astype(np.float16))
+
+    # step 0 eagerly on both (also the first use of the kernels outside any capture)
+    k1, v1, q = inputs(0)
+    k_in.copy_(k1); v_in.copy_(v1); q_in.copy_(q)
+    iq.innerq_decode_step_ragged(caches[0], counters[0], bound, k_in, v_in, q_in, ws[0], out=out_graph)
+    ref = iq.innerq_decode_step_ragged(caches[1], counters[1], bound, k1, v1, q, ws[1])
+    torch.cuda.synchronize()
+    assert torch.equal(out_graph, ref)
+    graph = torch.cuda.CUDAGraph()
+    k1, v1, q = inputs(1)
+    k_in.copy_(k1); v_in.copy_(v1); q_in.copy_(q)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        iq.innerq_decode_step_ragged(caches[0], counters[0], bound, k_in, v_in, q_in, ws[0], out=out_graph)
+    for i in range(1, n_steps):
+        k1, v1, q = inputs(i) if i > 1 else (k1, v1, q)
+        k_in.copy_(k1); v_in.copy_(v1); q_in.copy_(q)
+        graph.replay()
+        ref = iq.innerq_decode_step_ragged(caches[1], counters[1], bound, k1, v1, q, ws[1])     # eager work in between
+        torch.cuda.synchronize()
+        assert torch.equal(out_graph, ref), f"replay {i}"
+        assert counters[0].cpu().tolist() == [n + i + 1 for n in lengths] == counters[1].cpu().tolist()
+    for name in caches[0].buffers:
+        if caches[0].buffers[name] is not None:
+            assert torch.equal(caches[0].buffers[name], caches[1].buffers[name]), name
