@@ -65,6 +65,10 @@ def parse():
     p.add_argument("--sparse-zeros", action="store_true",
                    help="value zero-points are read only where a group is flagged asymmetric "
                         "(innerq_config_t.sparse_zeros = 1)")
+    p.add_argument("--paged", default=None, choices=["shuffled", "identity"],
+                   help="keep the quantised store in 64-row pages named by a page table (inner layout only): "
+                        "shuffled = every block on a random page of the pool; identity = pages in order, which "
+                        "isolates the cost of the lookup from the cost of the scatter")
     p.add_argument("--prefill", action="store_true",
                    help="time the prefill-side calls instead (key-norm calibration and the bulk append that "
                         "quantises a whole prompt) and print their rates; exits without the decode loop")
@@ -144,12 +148,18 @@ def crafted_groups(torch, gen, lead, G, bits, frac, device="cuda", return_mask=F
     return (x, is_asym) if return_mask else x
 
 
-def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None):
+def make_instance(torch, iq, w, cfg, layer, n_prefill, gen, asym_frac=None, shuffle_pages=True):
     """One cache filled with n_prefill synthetic tokens (values per the workload recipe, drawn on the device)."""
     B, Hk, d = w.batch, w.n_kv_heads, w.head_dim
     from paper_2602_23200_amd import workloads as wl
     sigma = torch.from_numpy(wl.key_channel_sigma(w, layer)).to("cuda", torch.float32)      # [Hk, d]
-    cache = iq.allocate_cache(cfg)
+    table = None
+    if cfg.page_pool_pages > 0:
+        # every 64-row block of every sequence on a page of its own, the pages in random order
+        table = (torch.randperm(cfg.page_pool_pages, device="cuda", generator=gen) if shuffle_pages
+                 else torch.arange(cfg.page_pool_pages, device="cuda")).to(torch.int32)
+        table = table.view(B, cfg.capacity_tokens // 64).contiguous()
+    cache = iq.allocate_cache(cfg, page_table=table)
     if asym_frac is not None:
         G = w.group
         # keys: groups of G channels of one token; values: groups of G tokens of one channel,
@@ -380,15 +390,21 @@ def main():
     # warm-up, pre-warm, the timed passes, the pass with events, and the breakdown passes (each at most 220 calls)
     max_steps = W + PREWARM_MAX_STEPS + (K + TIMED_MAX_STEPS) + max(K, 100) + 500
     per_inst_appends = (-(-max_steps // n_inst) + 2 if n_layers == 1 else max_steps + 2)
-    cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // w.group) * w.group
+    cap = -(-(w.n_tokens + per_inst_appends + 2 * w.group) // 64) * 64
+    if args.paged and (args.asym_frac is not None or args.sparse_zeros):
+        sys.exit("bench.py: --paged is not combined with --asym-frac / --sparse-zeros")
+    if args.paged and args.kind != "inner":
+        sys.exit("bench.py: --paged times the inner-grouped kernel (the comparison kernels read the contiguous store only)")
     cfg = iq.make_config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.group, w.w_sink,
-                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits, int(args.sparse_zeros))
+                         w.w_recent, w.k_mode, w.v_mode, 0, kind_id, cap, args.v_bits, int(args.sparse_zeros),
+                         w.batch * (cap // 64) if args.paged else 0)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
     if args.prefill:
         prefill_rates(torch, iq, w, cfg, gen)
         return
-    caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen, args.asym_frac)
+    caches = [make_instance(torch, iq, w, cfg, i if n_layers > 1 else 0, w.n_tokens - 1, gen, args.asym_frac,
+                             shuffle_pages=args.paged != "identity")
               for i in range(n_inst)]
     B, Hq, Hk, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
     flag_density = None
@@ -599,7 +615,7 @@ def main():
                    "step_mode": args.step_mode, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hk,
                    "head_dim": d, "context": w.n_tokens, "context_at_end": n_ctx_end, "bits": w.bits,
                    "v_bits": args.v_bits or w.bits,
-                   "sparse_zeros": int(args.sparse_zeros),
+                   "sparse_zeros": int(args.sparse_zeros), "paged_store": args.paged,
                    **({"asym_frac_requested": args.asym_frac, "asym_frac_measured": flag_density}
                       if flag_density is not None else {}),
                    "group": w.group, "w_sink": w.w_sink, "w_recent": w.w_recent,

@@ -118,6 +118,15 @@ typedef struct {
                               only where its group's flag is set, so 128-byte lines of zero-points that hold no
                               asymmetric group are never fetched (Section "Sparsity of M": the paper measures
                               about 1 % asymmetric groups and leaves exploiting that to future work). */
+  int64_t page_pool_pages; /* 0: the quantised store is contiguous per sequence (the layout above).
+                              > 0: a paged store (this library's own; Section "Limitations and Future Work"
+                              leaves integration with serving systems open).  The six store buffers
+                              (codes, scales, zeros of K and V) are then pools of this many pages.  A page holds
+                              64 consecutive store rows of one sequence for all kv heads, in the layout above
+                              read with B = page_pool_pages and capacity = 64; cache->page_table names the page
+                              of every 64-row block of every sequence.  capacity_tokens must be a multiple of
+                              64 and is then only the most tokens ONE sequence may hold (the length of a
+                              page-table row); the windows (sink, recent) stay per sequence. */
 } innerq_config_t;
 
 typedef struct {
@@ -133,6 +142,15 @@ typedef struct {
                                          which innerq_decode_attention_next and innerq_decode_step require.
                                          Zero-initialise it with the struct; to reuse the buffers for a new
                                          sequence set it and n_tokens back to 0. */
+  const int32_t *page_table;          /* device, int32 [B][capacity_tokens / 64], 4-byte aligned; read only when
+                                         cfg->page_pool_pages > 0 (else may be NULL).  Entry [b][j] is the pool page
+                                         that holds store rows 64 j .. 64 j + 63 of sequence b.  Owned and filled by
+                                         the caller (the allocator is the serving system's): before a call, every
+                                         block the store reaches after that call (rows below the quantised count of
+                                         innerq_partition, for the token count the call leaves, plus one token for the
+                                         calls that run the store a step ahead) must name a page no other live block
+                                         uses.  Entries beyond that are not read for data; an entry outside
+                                         [0, page_pool_pages) is clamped into the pool, never followed out of it. */
 } innerq_cache_t;
 
 typedef enum {

@@ -30,11 +30,13 @@ class innerq_config_t(C.Structure):
                 ("head_dim", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
                 ("w_sink", C.c_int32), ("w_recent", C.c_int32), ("k_mode", C.c_int32),
                 ("v_mode", C.c_int32), ("sym_denominator", C.c_int32), ("kind", C.c_int32),
-                ("capacity_tokens", C.c_int64), ("v_bits", C.c_int32), ("sparse_zeros", C.c_int32)]
+                ("capacity_tokens", C.c_int64), ("v_bits", C.c_int32), ("sparse_zeros", C.c_int32),
+                ("page_pool_pages", C.c_int64)]
 
 
 class innerq_cache_t(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES] + [("n_tokens", C.c_int64), ("store_ahead_tokens", C.c_int64)]
+    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES] + [("n_tokens", C.c_int64), ("store_ahead_tokens", C.c_int64),
+                                                           ("page_table", C.c_void_p)]
 
 
 class InnerQError(RuntimeError):
@@ -109,9 +111,9 @@ def status_string(status: int) -> str:
 
 def make_config(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
                 k_mode=HYBRID, v_mode=HYBRID, sym_denominator=0, kind=KIND_INNER,
-                capacity_tokens=0, v_bits=0, sparse_zeros=0) -> innerq_config_t:
+                capacity_tokens=0, v_bits=0, sparse_zeros=0, page_pool_pages=0) -> innerq_config_t:
     return innerq_config_t(batch, n_q_heads, n_kv_heads, head_dim, bits, group, w_sink, w_recent,
-                           k_mode, v_mode, sym_denominator, kind, capacity_tokens, v_bits, sparse_zeros)
+                           k_mode, v_mode, sym_denominator, kind, capacity_tokens, v_bits, sparse_zeros, page_pool_pages)
 
 
 def innerq_validate_config(cfg: innerq_config_t) -> int:
@@ -159,8 +161,10 @@ class Cache:
         return self.buffers[name].view(dtype).view(*shape)
 
 
-def allocate_cache(cfg: innerq_config_t, device="cuda") -> Cache:
-    """Allocate every buffer the configuration needs, sized by innerq_buffer_bytes, zero-filled."""
+def allocate_cache(cfg: innerq_config_t, device="cuda", page_table=None) -> Cache:
+    """Allocate every buffer the configuration needs, sized by innerq_buffer_bytes, zero-filled.
+    page_table: for a paged store (cfg.page_pool_pages > 0), the caller's int32 [B, capacity_tokens / 64]
+    tensor on the device; the cache keeps a reference to it."""
     import torch
     st = innerq_validate_config(cfg)
     if st != OK:
@@ -172,6 +176,11 @@ def allocate_cache(cfg: innerq_config_t, device="cuda") -> Cache:
         setattr(c, name, _ptr(bufs[name]))
     c.n_tokens = 0
     c.store_ahead_tokens = 0
+    if cfg.page_pool_pages > 0:
+        assert page_table is not None and page_table.dtype == torch.int32 and page_table.is_contiguous()
+        assert tuple(page_table.shape) == (cfg.batch, cfg.capacity_tokens // 64)
+        bufs["page_table"] = page_table
+        c.page_table = _ptr(page_table)
     return Cache(cfg, bufs, c)
 
 
@@ -320,6 +329,7 @@ def sequence_view(cache: Cache, b: int) -> Cache:
     is laid out [B][...], so a sequence is one contiguous slice of each."""
     from dataclasses import replace as _replace
     cfg = innerq_config_t.from_buffer_copy(bytes(cache.cfg))
+    assert cfg.page_pool_pages == 0, "the buffers of a paged store are pools, not per-sequence slices"
     B = cfg.batch
     cfg.batch = 1
     bufs, c = {}, innerq_cache_t()

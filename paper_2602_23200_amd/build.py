@@ -22,6 +22,7 @@ SOURCES = {
     "attention_outer.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
     # no NaN canonicalisation around fmax; MFMA results straight into VGPRs
     "attention_inner.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "attention_inner_paged.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
     "attention_inner_f4.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 

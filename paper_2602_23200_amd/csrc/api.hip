@@ -51,6 +51,8 @@ int check_config(const innerq_config_t* c) {
   if (c->v_bits != 0 && c->v_bits != 2 && c->v_bits != 3 && c->v_bits != 4) return INNERQ_E_UNSUPPORTED;
   if (c->group != 32 && c->group != 64) return INNERQ_E_UNSUPPORTED;
   if (c->sparse_zeros != 0 && c->sparse_zeros != 1) return INNERQ_E_ARG;
+  if (c->page_pool_pages < 0 || c->page_pool_pages > 0x7fffffffLL) return INNERQ_E_ARG;
+  if (c->page_pool_pages > 0 && c->capacity_tokens % kPageTokens != 0) return INNERQ_E_ARG;
   return INNERQ_OK;
 }
 
@@ -73,6 +75,10 @@ int check_cache(const innerq_config_t& c, const innerq_cache_t* k) {
   for (const void* p : ptrs)
     if (p && misaligned(p)) return INNERQ_E_ALIGN;
   if (k->n_tokens < 0 || k->n_tokens > c.capacity_tokens) return INNERQ_E_ARG;
+  if (c.page_pool_pages > 0) {
+    if (!k->page_table) return INNERQ_E_NULL;
+    if (reinterpret_cast<uintptr_t>(k->page_table) & 3u) return INNERQ_E_ALIGN;
+  }
   return INNERQ_OK;
 }
 
@@ -91,6 +97,14 @@ TensorView view_of(const innerq_config_t& c, const innerq_cache_t& k, int which,
   v.bits = bits_of(c, which);
   v.n_quant = p.n_quant;
   return v;
+}
+
+PageMap pages_of(const innerq_config_t& c, const innerq_cache_t& k) {
+  PageMap pm;
+  pm.table = c.page_pool_pages > 0 ? static_cast<const int*>(k.page_table) : nullptr;
+  pm.tiles_per_seq = (int)(c.capacity_tokens / kPageTokens);
+  pm.pool_pages = (int)c.page_pool_pages;
+  return pm;
 }
 
 // Compute units of the current device (queried once per device; a host-side attribute read).
@@ -143,17 +157,20 @@ const char* innerq_status_string(int status) {
 size_t innerq_buffer_bytes(const innerq_config_t* cfg, int which) {
   if (check_config(cfg) != INNERQ_OK || which < 0 || which >= INNERQ_BUF_COUNT) return 0;
   const innerq_config_t& c = *cfg;
-  const size_t BH = (size_t)c.batch * c.n_kv_heads, d = (size_t)c.head_dim, cap = (size_t)c.capacity_tokens;
+  const size_t BH = (size_t)c.batch * c.n_kv_heads, d = (size_t)c.head_dim;
+  // rows of the quantised store, over all sequences and kv heads (paged: over all pages of the pool)
+  const size_t rows = c.page_pool_pages > 0 ? (size_t)c.page_pool_pages * c.n_kv_heads * kPageTokens
+                                            : BH * (size_t)c.capacity_tokens;
   const int t = (which == INNERQ_BUF_K_CODES || which == INNERQ_BUF_K_SCALES || which == INNERQ_BUF_K_ZEROS ||
                  which == INNERQ_BUF_K_SINK || which == INNERQ_BUF_K_RECENT) ? 0 : 1;
   const int form = form_of(c.kind, t);
   switch (which) {
     case INNERQ_BUF_K_CODES: case INNERQ_BUF_V_CODES:
-      return form == kFp16 ? BH * cap * d * 2 : BH * cap * d * (size_t)bits_of(c, t) / 8;
+      return form == kFp16 ? rows * d * 2 : rows * d * (size_t)bits_of(c, t) / 8;
     case INNERQ_BUF_K_SCALES: case INNERQ_BUF_V_SCALES:
-      return form == kFp16 ? 0 : BH * cap * d / (size_t)c.group * 2;
+      return form == kFp16 ? 0 : rows * d / (size_t)c.group * 2;
     case INNERQ_BUF_K_ZEROS: case INNERQ_BUF_V_ZEROS:
-      return uses_zeros(c, t) ? BH * cap * d / (size_t)c.group * 2 : 0;
+      return uses_zeros(c, t) ? rows * d / (size_t)c.group * 2 : 0;
     case INNERQ_BUF_K_SINK: case INNERQ_BUF_V_SINK:
       return BH * (size_t)c.w_sink * d * 2;
     default:
@@ -210,6 +227,7 @@ static QuantArgs quant_args(const innerq_config_t* cfg, const innerq_cache_t* ca
   a.w_sink = cfg->w_sink; a.sym_den_literal = cfg->sym_denominator;
   a.capacity = cfg->capacity_tokens; a.n_old = n0; a.t_new = t_new;
   a.w_recent = cfg->w_recent; a.n_dev = nullptr; a.n_dev_out = nullptr;
+  a.pages = pages_of(*cfg, *cache);
   for (int w = 0; w < 2; ++w) {
     QuantTensorJob& j = a.job[w];
     j.is_keys = w == 0;
@@ -340,6 +358,7 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
   a.sparse_zeros = c.sparse_zeros;
   a.n_dev = n_dev;
   a.n_copy = n_dev ? static_cast<int*>(workspace) : nullptr;
+  a.pages = pages_of(c, *cache);
 
   // Tokens [w_sink, w_sink + n_both) are in the quantised store for both K and V: the split-K
   // range.  Everything else (sink window, recent windows, and the < G tokens quantised in only

@@ -183,7 +183,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool attention_fp16_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
-  return a.k.form == kFp16 && a.v.form == kFp16 && r <= 8 && a.capacity * D <= (1LL << 31);
+  return a.k.form == kFp16 && a.v.form == kFp16 && r <= 8 && a.capacity * D <= (1LL << 31) && !a.pages.table;
 }
 
 int attention_fp16_waves_per_cu(const AttnArgs& a) {

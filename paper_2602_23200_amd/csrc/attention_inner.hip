@@ -35,11 +35,20 @@
 //     resident at once at two per SIMD; contiguous tile ranges; two register
 //     buffers in ping-pong; the wavefront that is behind its SIMD partner gets the
 //     higher issue priority, so both finish together.
+//   * paged store: this file is compiled twice.  attention_inner_paged.hip includes it with
+//     INNERQ_PAGED_STORE set and gets the kernels that look every tile up in the page table (a page is
+//     one 64-token tile); the build for the contiguous store carries no trace of that.
 #include "innerq_dev.h"
 #include "window_pass.h"
 
+#ifndef INNERQ_PAGED_STORE
+#define INNERQ_PAGED_STORE 0
+#endif
+
 namespace innerq {
 namespace {
+
+constexpr bool kPagedStore = INNERQ_PAGED_STORE != 0;
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -126,6 +135,7 @@ struct TileRegs {
   uint32_t ks[NG / 2], kz[NG / 2];                     // fp16 pairs
   uint32_t vw[GPT][VW];
   uint32_t vs[GPT], vz[GPT];                           // fp16 pairs (this lane's two channels)
+  long long gshift;                                    // paged store: where the tile's value groups sit (wave-uniform)
   __device__ uint32_t k_word(int w) const { return kc[w / 4][w % 4]; }                 // (low) plane of the row
   __device__ uint32_t k_high(int w) const { return kc[(D * 2 / 32 + w) / 4][(D * 2 / 32 + w) % 4]; }
   __device__ uint32_t v_word(int gi, int ch, int w) const { return vw[gi][ch * CW + w]; }
@@ -227,19 +237,52 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(16))) _Float16 pA1[HIV ? NH * TILE : 8];
 
   // ---- per-(b, hk) base pointers
-  const uint8_t* kcodes = a.k.codes + bh * a.capacity * (D * KB / 8);
-  const __half* kscales = a.k.scales + bh * a.capacity * NG;
-  const __half* kzeros = has_kz ? a.k.zeros + bh * a.capacity * NG : nullptr;
-  const long long vgroups = a.capacity / G;
-  const uint8_t* vcodes = a.v.codes + bh * vgroups * D * (G * VB / 8);
-  const __half* vscales = a.v.scales + bh * vgroups * D;
-  const __half* vzeros = has_vz ? a.v.zeros + bh * vgroups * D : nullptr;
+  const long long slab = kPagedStore ? 0 : bh * a.capacity;             // first store row of (b, hk); paged: see below
+  const uint8_t* kcodes_slab = a.k.codes + slab * (D * KB / 8);
+  const __half* kscales_slab = a.k.scales + slab * NG;
+  const __half* kzeros_slab = has_kz ? a.k.zeros + slab * NG : nullptr;
+  const long long vgroups = slab / G;
+  const uint8_t* vcodes_slab = a.v.codes + vgroups * D * (G * VB / 8);
+  const __half* vscales_slab = a.v.scales + vgroups * D;
+  const __half* vzeros_slab = has_vz ? a.v.zeros + vgroups * D : nullptr;
   const int last_row = n_both - 1, last_group = n_both / G - 1;
   constexpr int ROWB = D * KB / 8;                     // bytes of one key row
   constexpr int GB = G * VB / 8;                       // bytes of one channel of one value group
 
+  // Paged store: a tile is one page (kPageTokens == TILE), so the tile's rows sit `shift` rows away
+  // from where the contiguous layout of a pool-sized cache would put rows tile * 64 .. of (b = 0, hk = 0):
+  // a wave-uniform 64-bit shift of the six bases, looked up once per tile.
+  static_assert(kPageTokens == TILE, "a page of the store is one tile of this kernel");
+  // The table entries of this wavefront's tiles come in one vector load, lane i holding the entry of
+  // tile pages_from + i (a wavefront with more than 64 tiles reloads every 64), and a tile reads its
+  // entry with a lane read.  (A scalar load per tile, even issued a tile ahead, costs more: scalar loads
+  // return out of order, so the first wait for an LDS operation behind it waits for the load as well.)
+  constexpr bool paged = kPagedStore;
+  int pages_from = t0, pages_held = 0;
+  auto fetch_pages = [&](int from) {
+    const int tile = from + lane < t1 ? from + lane : t1 - 1;
+    pages_from = from;
+    pages_held = a.pages.table[(long long)b * a.pages.tiles_per_seq + tile];
+  };
+  if constexpr (paged) {
+    if (t1 > t0) fetch_pages(t0);
+  }
+
   // All offsets inside one (b, hk) slab fit 32 bits; bases are wave-uniform.
   auto load_tile = [&](int tile, Regs& t) {
+    const uint8_t *kcodes = kcodes_slab, *vcodes = vcodes_slab;
+    const __half *kscales = kscales_slab, *kzeros = kzeros_slab, *vscales = vscales_slab, *vzeros = vzeros_slab;
+    if constexpr (paged) {
+      if (tile - pages_from >= 64) fetch_pages(tile);
+      int page = __builtin_amdgcn_readlane(pages_held, tile - pages_from);
+      page = page < 0 ? 0 : (page >= a.pages.pool_pages ? a.pages.pool_pages - 1 : page);
+      const long long shift = (((long long)page * a.n_kv_heads + hk) - tile) * TILE, gshift = shift / G * D;
+      kcodes += shift * ROWB; kscales += shift * NG;
+      if constexpr (has_kz) kzeros += shift * NG;
+      vcodes += gshift * GB; vscales += gshift;
+      if constexpr (has_vz) vzeros += gshift;
+      t.gshift = gshift;
+    }
     int row = tile * TILE + lane;
     row = row > last_row ? last_row : row;
     const u32x4* kp = reinterpret_cast<const u32x4*>(kcodes + (uint32_t)row * ROWB);
@@ -396,13 +439,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // needed at the end of the tile
     uint32_t vz_late[GPT];
     if constexpr (late_vz) {
+      const __half* vz_tile = vzeros_slab;
+      if constexpr (paged) vz_tile += cur.gshift;
 #pragma unroll
       for (int gi = 0; gi < GPT; ++gi) {
         int grp = tile * GPT + gi;
         grp = grp > last_group ? last_group : grp;
         vz_late[gi] = 0u;
         if (cur.vs[gi] & 0x80008000u)
-          vz_late[gi] = stream_load(reinterpret_cast<const uint32_t*>(vzeros + (uint32_t)grp * D + 2 * lane));
+          vz_late[gi] = stream_load(reinterpret_cast<const uint32_t*>(vz_tile + (uint32_t)grp * D + 2 * lane));
       }
     }
     // ================= scores: lane = token (Eq. att:1 with Eq. hybrid_dequant fused) =================
@@ -734,21 +779,12 @@ int resident_t(const AttnArgs& a) {
   return zv == 2 ? resident_z<KB, VB, G, false, 2>(a) : zv == 1 ? resident_z<KB, VB, G, false, 1>(a) : resident_z<KB, VB, G, false, 0>(a);
 }
 
-}  // namespace
-
 // Width pairs (keys, values) the fused kernel is built for: equal widths, and the paper's
 // Hybrid / Small presets (3-bit keys, 2-bit values).
 inline int width_pair(const AttnArgs& a) {
   if (a.bits == a.v_bits && a.bits >= 2 && a.bits <= 4) return a.bits - 2;   // 0, 1, 2
   if (a.bits == 3 && a.v_bits == 2) return 3;
   return -1;
-}
-
-bool attention_inner_supported(const AttnArgs& a) {
-  const int r = a.n_q_heads / a.n_kv_heads;
-  // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
-  return a.k.form == kPerToken && a.v.form == kPerChannel && width_pair(a) >= 0 && r <= 8 &&
-         (a.group == 32 || a.group == 64) && a.capacity * D <= (1LL << 31);
 }
 
 // Calls f.template operator()<KB, VB, G>() for the configuration's widths and group size.
@@ -778,12 +814,8 @@ struct LaunchFn {
   hipError_t operator()() const { return launch_t<KB, VB, G>(a, n_both, n_splits, win, L); }
 };
 
-std::atomic<int> g_inner_variant{0};
-
-int attention_inner_waves_per_cu(const AttnArgs& a) {
-  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a) && !a.n_dev)
-    return attention_inner_f4_waves_per_cu(a);
-  // cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
+// cached per (widths, group, zero flags, head tile): the answer depends on the kernel instance only
+int waves_per_cu_of_this_build(const AttnArgs& a) {
   static CachedInt cache[4][2][2][3][2];
   const int r = a.n_q_heads / a.n_kv_heads;
   const int wp = width_pair(a);
@@ -792,13 +824,47 @@ int attention_inner_waves_per_cu(const AttnArgs& a) {
       [&] { return for_widths(a, ResidentFn{a}); });
 }
 
+}  // namespace
+
+#if INNERQ_PAGED_STORE
+
+int attention_inner_paged_waves_per_cu(const AttnArgs& a) { return waves_per_cu_of_this_build(a); }
+
+hipError_t launch_attention_inner_paged(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
+                                        hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if (!a.pages.table || !attention_inner_supported(a)) return hipErrorInvalidValue;
+  const Launch L = {stream, ev_start, ev_stop};
+  return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});
+}
+
+#else
+
+bool attention_inner_supported(const AttnArgs& a) {
+  const int r = a.n_q_heads / a.n_kv_heads;
+  // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
+  return a.k.form == kPerToken && a.v.form == kPerChannel && width_pair(a) >= 0 && r <= 8 &&
+         (a.group == 32 || a.group == 64) && a.capacity * D <= (1LL << 31);
+}
+
+std::atomic<int> g_inner_variant{0};
+
+int attention_inner_waves_per_cu(const AttnArgs& a) {
+  if (a.pages.table) return attention_inner_paged_waves_per_cu(a);
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
+    return attention_inner_f4_waves_per_cu(a);
+  return waves_per_cu_of_this_build(a);
+}
+
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both_ll, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!attention_inner_supported(a)) return hipErrorInvalidValue;
-  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a) && !a.n_dev)
+  if (a.pages.table) return launch_attention_inner_paged(a, n_both_ll, n_splits, win, stream, ev_start, ev_stop);
+  if (g_inner_variant.load(std::memory_order_relaxed) == 1 && attention_inner_f4_supported(a))
     return launch_attention_inner_f4(a, n_both_ll, n_splits, win, stream, ev_start, ev_stop);
   const Launch L = {stream, ev_start, ev_stop};
   return for_widths(a, LaunchFn{a, (int)n_both_ll, n_splits, win, L});
 }
+
+#endif
 
 }  // namespace innerq

@@ -615,7 +615,7 @@ bool attention_inner_f4_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   // offsets inside one (batch, kv-head) slab are 32-bit in the kernel
   return a.k.form == kPerToken && a.v.form == kPerChannel && a.bits == 2 && a.v_bits == 2 && r <= 4 &&
-         (a.group == 32 || a.group == 64) && a.capacity * D <= (1LL << 31);
+         (a.group == 32 || a.group == 64) && a.capacity * D <= (1LL << 31) && !a.pages.table && !a.n_dev;
 }
 
 int attention_inner_f4_waves_per_cu(const AttnArgs& a) {

@@ -371,7 +371,7 @@ hipError_t launch_t(const AttnArgs& a, int n_both, int n_splits, const WindowSet
 bool attention_outer_supported(const AttnArgs& a) {
   const int r = a.n_q_heads / a.n_kv_heads;
   return a.k.form == kPerChannel && a.v.form == kPerToken && (a.bits == 2 || a.bits == 4) && a.v_bits == a.bits && r <= 8 &&
-         a.capacity * D <= (1LL << 31);
+         a.capacity * D <= (1LL << 31) && !a.pages.table;
 }
 
 int attention_outer_waves_per_cu(const AttnArgs& a) {

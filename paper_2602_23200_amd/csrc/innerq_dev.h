@@ -17,6 +17,28 @@ constexpr int kHeadDim = 128;          // the only head_dim built
 constexpr int kWindowChunk = 64;       // most window tokens per wavefront / work-group chunk
 constexpr int kWindowChunkMin = 16;    // fewest (short contexts, slots to spare)
 constexpr int kHeadTile = 4;           // query heads served by one work-group pass
+constexpr int kPageTokens = 64;        // tokens per page of a paged store (= one tile of the fused kernels)
+
+// A paged store (no counterpart in the paper, which leaves memory management to future work): the six
+// store buffers are pools of pages of 64 token rows, laid out like the contiguous store of a cache with
+// batch = pool pages and capacity = 64, and table[b][r / 64] names the page that holds store row r of
+// sequence b.  table == null: the contiguous store.
+struct PageMap {
+  const int* table;        // device, [B][tiles_per_seq]
+  int tiles_per_seq;       // capacity_tokens / 64
+  int pool_pages;          // page ids are clamped to [0, pool_pages): a bad entry cannot leave the buffers
+};
+// Linear row index, in the store buffers, of store row `row` of sequence-head bh (a row of the per-token
+// form; row / G is the linear group index of the per-channel form when row is a multiple of G).
+__device__ __forceinline__ long long store_row(const PageMap& pm, int n_kv_heads, long long capacity, long long bh,
+                                               long long row) {
+  if (!pm.table) return bh * capacity + row;
+  const uint32_t b = (uint32_t)bh / (uint32_t)n_kv_heads, hk = (uint32_t)bh % (uint32_t)n_kv_heads;
+  int page = pm.table[(long long)b * pm.tiles_per_seq + (row >> 6)];
+  page = page < 0 ? 0 : (page >= pm.pool_pages ? pm.pool_pages - 1 : page);
+  return ((long long)page * n_kv_heads + hk) * kPageTokens + (row & 63);
+}
+
 
 enum Form : int { kPerToken = 0, kPerChannel = 1, kFp16 = 2 };
 
@@ -105,6 +127,7 @@ struct QuantArgs {
   int w_recent;
   const int* n_dev;
   int* n_dev_out;
+  PageMap pages;
 };
 
 struct AttnArgs;
@@ -132,6 +155,7 @@ struct AttnArgs {
   // kernel leaves a copy of them for the append that follows in the same step (workspace, [B])
   const int* n_dev;
   int* n_copy;
+  PageMap pages;
 };
 
 // Generic (any form, element-by-element) partial attention over the token set
@@ -154,6 +178,12 @@ int attention_inner_waves_per_cu(const AttnArgs& a);   // resident wavefronts pe
 struct Launch { hipStream_t stream; hipEvent_t ev_start, ev_stop; };
 hipError_t launch_attention_inner(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+
+// The same kernels compiled for a paged store (a.pages.table set); launch_attention_inner and
+// attention_inner_waves_per_cu route there.
+int attention_inner_paged_waves_per_cu(const AttnArgs& a);
+hipError_t launch_attention_inner_paged(const AttnArgs& a, long long n_both, int n_splits, const WindowSet& win,
+                                        hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // The same partial results for 2-bit codes from the block-scaled fp8 x fp4 matrix instruction
 // (128-token tiles).  Parity-green but slower than the 4x4x4 form (see the file header), so it runs

@@ -397,14 +397,15 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     // a row is one plane of LB-bit fields over all channels (3-bit: followed by the plane of high bits)
     constexpr int LB = BITS == 3 ? 2 : BITS;
     constexpr int WL = G * LB / 32;                      // words of the (low) plane of one group
-    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8);
+    const long long lin = store_row(a.pages, a.n_kv_heads, a.capacity, bh, row);
+    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + (lin * kHeadDim * BITS) / 8);
 #pragma unroll
     for (int i = 0; i < WL; ++i) rowp[g * WL + i] = words[i];
     if constexpr (BITS == 3) {
 #pragma unroll
       for (int i = 0; i < G / 32; ++i) rowp[kHeadDim * 2 / 32 + g * (G / 32) + i] = words[WL + i];
     }
-    const long long so = (bh * a.capacity + row) * GPR + g;
+    const long long so = lin * GPR + g;
     j.scales[so] = s;
     if (j.zeros) j.zeros[so] = z;
   } else if (j.form == kPerToken) {
@@ -444,14 +445,15 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
     uint32_t word_hi;
     const uint32_t word = quantize_group_lanes<G, BITS>(x, sub, j.mode, a.sym_den_literal, s, z, word_hi);
     // a row is one plane of LB-bit fields over all channels (3-bit: followed by the plane of high bits)
-    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + ((bh * a.capacity + row) * kHeadDim * BITS) / 8);
+    const long long lin = store_row(a.pages, a.n_kv_heads, a.capacity, bh, row);
+    uint32_t* rowp = reinterpret_cast<uint32_t*>(j.codes + (lin * kHeadDim * BITS) / 8);
     if (sub % LPW == 0) rowp[g * (G * LB / 32) + sub / LPW] = word;
     if constexpr (BITS == 3) {
       constexpr int LPH = 32 / E;
       if (sub % LPH == 0) rowp[kHeadDim * 2 / 32 + g * (G / 32) + sub / LPH] = word_hi;
     }
     if (sub == 0) {
-      const long long so = (bh * a.capacity + row) * GPR + g;
+      const long long so = lin * GPR + g;
       j.scales[so] = s;
       if (j.zeros) j.zeros[so] = z;
     }
@@ -501,7 +503,7 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
         return v;
       });
     }
-    const long long go = (bh * (a.capacity / G) + tg) * kHeadDim + c;
+    const long long go = (store_row(a.pages, a.n_kv_heads, a.capacity, bh, tg * G) / G) * kHeadDim + c;
     uint32_t* dst = reinterpret_cast<uint32_t*>(j.codes) + go * W;
 #pragma unroll
     for (int i = 0; i < W; ++i) dst[i] = words[i];
@@ -525,7 +527,7 @@ __device__ __forceinline__ void quantize_rows(const QuantArgs& a, const QuantTen
 #pragma unroll
       for (int e = 0; e < 8; ++e) h[e] = scaled_half(h2f(h[e]), inv[e]);
     }
-    __half* dst = reinterpret_cast<__half*>(j.codes) + (bh * a.capacity + row) * kHeadDim + ch * 8;
+    __half* dst = reinterpret_cast<__half*>(j.codes) + store_row(a.pages, a.n_kv_heads, a.capacity, bh, row) * kHeadDim + ch * 8;
     *reinterpret_cast<uint4*>(dst) = raw;
   }
 }

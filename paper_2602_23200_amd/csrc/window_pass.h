@@ -23,7 +23,8 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
   if (t < tv.n_sink) return __half2float(tv.sink[(bh * a.w_sink + t) * D + c]);
   const long long row = t - a.w_sink;
   if (row >= tv.n_quant) return __half2float(tv.ring[(bh * tv.slots + (t % tv.slots)) * D + c]);
-  if (tv.form == kFp16) return __half2float(reinterpret_cast<const __half*>(tv.codes)[(bh * a.capacity + row) * D + c]);
+  const long long lin = store_row(a.pages, a.n_kv_heads, a.capacity, bh, row);     // (contiguous: bh * capacity + row)
+  if (tv.form == kFp16) return __half2float(reinterpret_cast<const __half*>(tv.codes)[lin * D + c]);
   const int bits = tv.bits, G = a.group;
   long long si;
   unsigned field;
@@ -34,11 +35,10 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
     return (p[(i * bits) / 8] >> ((i * bits) % 8)) & ((1u << bits) - 1u);
   };
   if (tv.form == kPerToken) {
-    field = field_of(tv.codes + ((bh * a.capacity + row) * D * bits) / 8, c, D);
-    si = (bh * a.capacity + row) * (D / G) + c / G;
+    field = field_of(tv.codes + (lin * D * bits) / 8, c, D);
+    si = lin * (D / G) + c / G;
   } else {
-    const long long tg = row / G;
-    si = (bh * (a.capacity / G) + tg) * D + c;
+    si = (store_row(a.pages, a.n_kv_heads, a.capacity, bh, row - row % G) / G) * D + c;
     field = field_of(tv.codes + si * ((G * bits) / 8), (int)(row % G), G);
   }
   const float s = __half2float(tv.scales[si]);
@@ -72,6 +72,8 @@ __device__ __forceinline__ const __half* fp16_row(const TensorView& tv, const At
   const __half* base_store = reinterpret_cast<const __half*>(tv.codes) + bh * a.capacity * D;
   const __half* base = is_new ? base_new : is_sink ? base_sink : is_ring ? base_ring : base_store;
   const uint32_t off = is_new ? 0u : is_sink ? tt * D : is_ring ? slot * D : row * D;
+  if (a.pages.table && is_store && !(is_new || is_sink || is_ring))       // an fp16 store kept in pages
+    return reinterpret_cast<const __half*>(tv.codes) + store_row(a.pages, a.n_kv_heads, a.capacity, bh, row) * D;
   return (is_new || is_sink || is_ring || is_store) ? base + off : nullptr;
 }
 
@@ -180,7 +182,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
       const __half* krow = fp16_row(a.k, a, bh, t);
       if (KQ && !krow) {
         k_packed = true;
-        const long long row = bh * a.capacity + (t - a.w_sink);
+        const long long row = store_row(a.pages, a.n_kv_heads, a.capacity, bh, t - a.w_sink);
         const w_u32x4* rowp = reinterpret_cast<const w_u32x4*>(a.k.codes + row * (D * BITS / 8));
 #pragma unroll
         for (int i = 0; i < KVEC; ++i) kreg[i] = rowp[i];
@@ -208,7 +210,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
       const __half* vrow = fp16_row(a.v, a, bh, tj);
       if (VQ && !vrow) {
         v_packed |= 1u << k;
-        const long long row = bh * a.capacity + (tj - a.w_sink);
+        const long long row = store_row(a.pages, a.n_kv_heads, a.capacity, bh, tj - a.w_sink);
         const int c0 = 8 * cg;
         const uint8_t* cp = a.v.codes + row * (D * BITS / 8) + (c0 * BITS) / 8;
         const long long si = row * NG + c0 / G;

@@ -43,11 +43,11 @@ def cfg_of(w, kind=iq.KIND_INNER, **over):
 
 def test_struct_layout_matches_header_order():
     # twelve int32, one int64, one int32 (+ tail padding to the int64 alignment)
-    assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8 + 8
+    assert C.sizeof(iq.innerq_config_t) == 12 * 4 + 8 + 8 + 8
     assert iq.innerq_config_t.capacity_tokens.offset == 48 and iq.innerq_config_t.v_bits.offset == 56
-    assert iq.innerq_config_t.sparse_zeros.offset == 60
-    assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8 + 8
-    assert iq.innerq_cache_t.store_ahead_tokens.offset == 88
+    assert iq.innerq_config_t.sparse_zeros.offset == 60 and iq.innerq_config_t.page_pool_pages.offset == 64
+    assert C.sizeof(iq.innerq_cache_t) == 10 * 8 + 8 + 8 + 8
+    assert iq.innerq_cache_t.store_ahead_tokens.offset == 88 and iq.innerq_cache_t.page_table.offset == 96
 
 
 def test_validate_config_rejections():
@@ -159,3 +159,33 @@ def test_static_workspace_entry_rejects_what_does_not_fit():
     assert L.innerq_decode_attention_static(C.byref(cfg), C.byref(cache), 4096, None, 4096, 1, None) == iq.E_WORKSPACE
     header = open(os.path.join(ROOT, "include", "innerq.h")).read()
     assert f"INNERQ_STATIC_WORKSPACE_BYTES ({iq.STATIC_WORKSPACE_BYTES >> 20}u << 20)" in header
+
+
+def test_paged_store_sizes_and_rejections():
+    """A paged store: the six store buffers are sized by the pool, the windows by the batch; the page table
+    is required and checked on the host."""
+    w = wl.WORKLOADS["tiny"]
+    c, o = cfg_of(w, capacity_tokens=1280)
+    store = ("k_codes", "k_scales", "k_zeros", "v_codes", "v_scales", "v_zeros")
+    flat = [iq.innerq_buffer_bytes(c, i) for i in range(len(iq.BUFFER_NAMES))]
+    c.page_pool_pages = 7
+    assert iq.innerq_validate_config(c) == iq.OK
+    paged = [iq.innerq_buffer_bytes(c, i) for i in range(len(iq.BUFFER_NAMES))]
+    for i, name in enumerate(iq.BUFFER_NAMES):
+        if name in store:
+            assert paged[i] * c.batch * (c.capacity_tokens // 64) == flat[i] * 7, name
+        else:
+            assert paged[i] == flat[i], name
+    L = iq.lib()
+    cache = iq.innerq_cache_t()
+    for n in iq.BUFFER_NAMES:
+        setattr(cache, n, 4096)
+    cache.n_tokens = 10
+    assert L.innerq_quantize_append(C.byref(c), C.byref(cache), 4096, 4096, 1, None, None) == iq.E_NULL
+    cache.page_table = 4098
+    assert L.innerq_decode_attention(C.byref(c), C.byref(cache), 4096, None, 4096, 1, 4096, 1 << 30, None) == iq.E_ALIGN
+    c.page_pool_pages = -1
+    assert iq.innerq_validate_config(c) == iq.E_ARG
+    c.page_pool_pages = 7
+    c.capacity_tokens = 1280 + 32                                   # not a whole number of pages
+    assert iq.innerq_validate_config(c) == iq.E_ARG
