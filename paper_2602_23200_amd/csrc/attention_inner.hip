@@ -236,6 +236,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(16))) _Float16 qA1[HIK ? NH * D : 8];
   __shared__ __attribute__((aligned(16))) _Float16 pA1[HIV ? NH * TILE : 8];
 
+  // A wavefront without a tile (a launch with more wavefronts than tiles gives the window chunks
+  // wavefronts of their own) skips all of the tile machinery, query tables included.
+  if (t1 > t0) {
   // ---- per-(b, hk) base pointers
   const long long slab = kPagedStore ? 0 : bh * a.capacity;             // first store row of (b, hk); paged: see below
   const uint8_t* kcodes_slab = a.k.codes + slab * (D * KB / 8);
@@ -657,6 +660,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   {
     const int n = t1 - t0;
     int i = 0;
+    // (one or two tiles only: ahead of the wavefronts that carry nothing but a window chunk)
+    if (n <= 2) __builtin_amdgcn_s_setprio(2);
     while (i + 2 < n) {
       // the wavefront that is behind gets the SIMD first: the two wavefronts of a SIMD then
       // finish together instead of one running alone (and at a lower rate) at the end
@@ -677,10 +682,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     } else if (n - i == 1) {
       process(bufA, t0 + i, i == 0);
     }
-    if (n <= 0) {                                       // no tile for this wavefront: an empty partial
-#pragma unroll
-      for (int h = 0; h < NH; ++h) m_run[h] = -INFINITY;
-    }
   }
 
   // ---- partial (m, l, o) of every real head
@@ -699,11 +700,22 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
   }
+  } else {
+    // ---- an empty partial
+    for (int h = 0; h < r; ++h) {
+      const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
+      *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + s_idx) * D + 2 * lane]) = float2{0.f, 0.f};
+      if (lane == 0) {
+        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 0] = -INFINITY;
+        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 1] = 0.f;
+      }
+    }
+  }
 
   // ---- the window chunk of this wavefront, with a partial slot of its own
   if (s_idx < win.n_chunks) {
-    __syncthreads();
-    window_pass<NH4, KB, G, true, false>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
+    __builtin_amdgcn_s_setprio(0);
+    window_pass<NH4, KB, G, true, false, kPagedStore>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
   }
 }
 

@@ -48,7 +48,8 @@ __device__ inline float fetch_element(const TensorView& tv, const AttnArgs& a, l
 }
 
 // fp16 row of token t if that tensor keeps it in fp16 (sink window, recent ring, fp16 store, or the
-// not yet appended newest token), else null.  Written for a caller that asks for many rows per
+// not yet appended newest token), else null.  For the contiguous store only (the fused kernels whose store is
+// fp16 do not take paged caches).  Written for a caller that asks for many rows per
 // lane: everything that depends on bh alone is wave-uniform (scalar registers), the per-lane part
 // is 32-bit (token indices stay below 2^24: capacity * head_dim <= 2^31), and the ring slot
 // t mod slots comes from a float reciprocal with a one-step correction instead of an integer
@@ -72,8 +73,6 @@ __device__ __forceinline__ const __half* fp16_row(const TensorView& tv, const At
   const __half* base_store = reinterpret_cast<const __half*>(tv.codes) + bh * a.capacity * D;
   const __half* base = is_new ? base_new : is_sink ? base_sink : is_ring ? base_ring : base_store;
   const uint32_t off = is_new ? 0u : is_sink ? tt * D : is_ring ? slot * D : row * D;
-  if (a.pages.table && is_store && !(is_new || is_sink || is_ring))       // an fp16 store kept in pages
-    return reinterpret_cast<const __half*>(tv.codes) + store_row(a.pages, a.n_kv_heads, a.capacity, bh, row) * D;
   return (is_new || is_sink || is_ring || is_store) ? base + off : nullptr;
 }
 
@@ -113,10 +112,18 @@ __device__ inline float window_half_hi(uint32_t w) { return __half2float(__ushor
 // for a full group: KQ says the key may be such a packed row (inner grouping), VQ the value
 // (outer grouping).  BITS and G describe those packed rows.
 //
-// Every global load of a 64-token step (the lane's key row, its 16 value-row pieces) is issued
+// Every global load of a 64-token step (the lane's key row, its pieces of the value rows) is issued
 // before any of them is used, so a step pays one memory round trip; the query set-up runs under
 // that round trip too.
-template <int NH4, int BITS, int G, bool KQ, bool VQ>
+//
+// Keys: lane = token.  Values without packed rows (!VQ): lane = a pair of channels, every token's row
+// read as one coalesced 256-byte load whose base address is wave-uniform -- each lane works out the
+// row address of its own token once and the loads fetch it from that lane -- and the weighted sums
+// come out of the matrix instructions already complete per lane (no reduction across lanes).  With
+// packed value rows (VQ): 16 lanes share a row, four rows per load, summed across the lane groups at
+// the end.
+// PAGED: the packed rows are looked up through the page table (else the table is never consulted).
+template <int NH4, int BITS, int G, bool KQ, bool VQ, bool PAGED = false>
 __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, long long na, long long b0,
                                             long long nb, int chunk, int n_chunks, int slot) {
   constexpr int D = kHeadDim;
@@ -140,8 +147,8 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   __shared__ __attribute__((aligned(16))) float wqf[KQ ? D : 1][NH];   // the same values as fp32, head fastest
   __shared__ __attribute__((aligned(16))) float wqs[NG][NH];        // their sums over each key group
   __shared__ __attribute__((aligned(16))) float wp[VQ ? 64 : 1][NH];   // probabilities of the current 64 tokens
-  // the same, rounded to fp16, as matrix operands: [token % 4][head][token / 4]
-  __shared__ __attribute__((aligned(16))) _Float16 wp16[VQ ? 1 : 4 * NH * 16];
+  // the same, rounded to fp16, as matrix operands: [head][token]
+  __shared__ __attribute__((aligned(16))) _Float16 wp16[VQ ? 4 : NH * 64];
 
   const int cg = lane & 15, tg = lane >> 4;
   // (every index here is below 2^24: 32-bit arithmetic per lane)
@@ -154,23 +161,26 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;    // log2(e) / sqrt(d)
   // o[h][e]: head h, channel 8 cg + e, the tokens 4 k + tg of every step.  Without packed value
   // rows the same sums are held as matrix-instruction results oq[e][n] (heads 4 n .. 4 n + 3).
-  float m_run[NH], l_run[NH], o[NH][8];
-  w_float4_t oq[8][NH4];
+  float m_run[NH], l_run[NH], o[VQ ? NH : 1][8];
+  w_float4_t oq[2][NH4];                   // (!VQ) [channel of the lane's pair][heads 4 n .. 4 n + 3]
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
     m_run[h] = -INFINITY;
     l_run[h] = 0.f;
+    if constexpr (VQ) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
+      for (int e = 0; e < 8; ++e) o[h][e] = 0.f;
+    }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e)
+  for (int e = 0; e < 2; ++e)
 #pragma unroll
     for (int n = 0; n < NH4; ++n) oq[e][n] = w_float4_t{0.f, 0.f, 0.f, 0.f};
 
   for (long long base = v0; base < v1; base += 64) {
     // ---- all loads of this step
-    w_u32x4 kreg[16], vreg[16];
+    w_u32x4 kreg[16], vreg[VQ ? 16 : 1];
+    uint32_t vw[VQ ? 1 : 64];                      // (!VQ) this lane's channel pair of every token of the step
     uint32_t ks[2] = {0u, 0u}, kz[2] = {0u, 0u};   // packed key row: scales and zero-points, fp16 pairs
     bool k_packed = false;
     uint32_t v_packed = 0u;                        // bit k: value row k of this lane is a packed row
@@ -182,7 +192,8 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
       const __half* krow = fp16_row(a.k, a, bh, t);
       if (KQ && !krow) {
         k_packed = true;
-        const long long row = store_row(a.pages, a.n_kv_heads, a.capacity, bh, t - a.w_sink);
+        const long long row = PAGED ? store_row(a.pages, a.n_kv_heads, a.capacity, bh, t - a.w_sink)
+                                    : bh * a.capacity + (t - a.w_sink);
         const w_u32x4* rowp = reinterpret_cast<const w_u32x4*>(a.k.codes + row * (D * BITS / 8));
 #pragma unroll
         for (int i = 0; i < KVEC; ++i) kreg[i] = rowp[i];
@@ -199,29 +210,51 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         for (int i = 0; i < 16; ++i) kreg[i] = *reinterpret_cast<const w_u32x4*>(krow + i * 8);
       }
     }
+    if constexpr (VQ) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      if (4 * k >= n_here) {                             // (uniform) no row left in this step
-        vreg[k] = w_u32x4{0u, 0u, 0u, 0u};               // meets weight 0 below: must be finite
-        continue;
+      for (int k = 0; k < 16; ++k) {
+        if (4 * k >= n_here) {                             // (uniform) no row left in this step
+          vreg[k] = w_u32x4{0u, 0u, 0u, 0u};               // meets weight 0 below: must be finite
+          continue;
+        }
+        const int j = 4 * k + tg;
+        const long long tj = token_of(base + (j < n_here ? j : n_here - 1));
+        const __half* vrow = fp16_row(a.v, a, bh, tj);
+        if (VQ && !vrow) {
+          v_packed |= 1u << k;
+          const long long row = PAGED ? store_row(a.pages, a.n_kv_heads, a.capacity, bh, tj - a.w_sink)
+                                      : bh * a.capacity + (tj - a.w_sink);
+          const int c0 = 8 * cg;
+          const uint8_t* cp = a.v.codes + row * (D * BITS / 8) + (c0 * BITS) / 8;
+          const long long si = row * NG + c0 / G;
+          w_u32x4 m = w_u32x4{0u, 0u, 0u, 0u};
+          if constexpr (BITS == 2) m.x = (uint32_t)*reinterpret_cast<const unsigned short*>(cp);
+          else m.x = *reinterpret_cast<const uint32_t*>(cp);
+          m.y = (uint32_t)__half_as_ushort(a.v.scales[si]);
+          if (a.v.zeros) m.z = (uint32_t)__half_as_ushort(a.v.zeros[si]);
+          vreg[k] = m;
+        } else {                                              // an fp16 row (always, unless VQ)
+          vreg[k] = *reinterpret_cast<const w_u32x4*>(vrow + 8 * cg);
+        }
       }
-      const int j = 4 * k + tg;
-      const long long tj = token_of(base + (j < n_here ? j : n_here - 1));
-      const __half* vrow = fp16_row(a.v, a, bh, tj);
-      if (VQ && !vrow) {
-        v_packed |= 1u << k;
-        const long long row = store_row(a.pages, a.n_kv_heads, a.capacity, bh, tj - a.w_sink);
-        const int c0 = 8 * cg;
-        const uint8_t* cp = a.v.codes + row * (D * BITS / 8) + (c0 * BITS) / 8;
-        const long long si = row * NG + c0 / G;
-        w_u32x4 m = w_u32x4{0u, 0u, 0u, 0u};
-        if constexpr (BITS == 2) m.x = (uint32_t)*reinterpret_cast<const unsigned short*>(cp);
-        else m.x = *reinterpret_cast<const uint32_t*>(cp);
-        m.y = (uint32_t)__half_as_ushort(a.v.scales[si]);
-        if (a.v.zeros) m.z = (uint32_t)__half_as_ushort(a.v.zeros[si]);
-        vreg[k] = m;
-      } else {                                              // an fp16 row (always, unless VQ)
-        vreg[k] = *reinterpret_cast<const w_u32x4*>(vrow + 8 * cg);
+    } else {
+      // the value row of this lane's token, as two 32-bit halves that the loads below read lane by lane
+      const uintptr_t vrow_own = reinterpret_cast<uintptr_t>(fp16_row(a.v, a, bh, token_of(valid ? v : v1 - 1)));
+      const int own_lo = (int)(uint32_t)vrow_own, own_hi = (int)(uint32_t)(vrow_own >> 32);
+#pragma unroll
+      for (int kq = 0; kq < 16; ++kq) {
+        if (4 * kq >= n_here) {                          // (uniform) no row left in this step
+#pragma unroll
+          for (int i = 0; i < 4; ++i) vw[4 * kq + i] = 0u;   // meets weight 0 below: must be finite
+          continue;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = 4 * kq + i < n_here ? 4 * kq + i : n_here - 1;     // rows past the end re-read the last one
+          const uintptr_t row = ((uintptr_t)(uint32_t)__builtin_amdgcn_readlane(own_hi, j) << 32) |
+                                (uintptr_t)(uint32_t)__builtin_amdgcn_readlane(own_lo, j);
+          vw[4 * kq + i] = reinterpret_cast<const uint32_t*>(row)[lane];
+        }
       }
     }
 
@@ -351,7 +384,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         // the weight the matrix cores will use, so that the normaliser stays consistent
         const _Float16 p16 = (_Float16)p;
         p = (float)p16;
-        wp16[((lane & 3) * NH + h) * 16 + (lane >> 2)] = p16;
+        wp16[h * 64 + lane] = p16;
       } else {
         wp[lane][h] = p;
       }
@@ -362,7 +395,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         for (int e = 0; e < 8; ++e) o[h][e] *= alpha;
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) oq[e][h / 4][h % 4] *= alpha;
+        for (int e = 0; e < 2; ++e) oq[e][h / 4][h % 4] *= alpha;
       }
     }
     __syncthreads();
@@ -370,31 +403,24 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     // instruction; a lane keeps o[head][8 channels] of the tokens (4k + lane/16) and the four
     // lane groups are summed at the end.  Rows past the end carry probability 0.
     if constexpr (!VQ) {
-      // matrix cores: contraction over four tokens (4 kq .. 4 kq + 3 of this lane group), B = one
-      // channel of this lane for those tokens (halves gathered from the four row registers),
-      // A = the fp16 weights of the four heads for the same tokens
+      // matrix cores: contraction over four tokens (4 kq .. 4 kq + 3), B = one channel of this lane
+      // for those tokens (halves gathered from the four row words), A = the fp16 weights of the four
+      // heads for the same tokens; the four results are the lane's own channel for the four heads
 #pragma unroll
-      for (int kq = 0; kq < 4; ++kq) {
-        if (16 * kq >= n_here) break;                    // (uniform) no row left in this step
-        w_half4_t aop[NH4];
+      for (int kq = 0; kq < 16; ++kq) {
+        if (4 * kq >= n_here) break;                     // (uniform) no row left in this step
+        const uint32_t w0 = vw[4 * kq], w1 = vw[4 * kq + 1], w2 = vw[4 * kq + 2], w3 = vw[4 * kq + 3];
+        w_u32x2 lo, hi;
+        lo.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);   // low halves: channel 2 lane of tokens 0, 1
+        lo.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+        hi.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);   // high halves: channel 2 lane + 1
+        hi.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+        const w_half4_t blo = __builtin_bit_cast(w_half4_t, lo), bhi = __builtin_bit_cast(w_half4_t, hi);
 #pragma unroll
-        for (int n = 0; n < NH4; ++n)
-          aop[n] = *reinterpret_cast<const w_half4_t*>(&wp16[(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
-#pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
-          const uint32_t w0 = vreg[4 * kq][wd], w1 = vreg[4 * kq + 1][wd], w2 = vreg[4 * kq + 2][wd],
-                         w3 = vreg[4 * kq + 3][wd];
-          w_u32x2 lo, hi;
-          lo.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);   // low halves: channel 2 wd of tokens 0, 1
-          lo.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
-          hi.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);   // high halves: channel 2 wd + 1
-          hi.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-          const w_half4_t blo = __builtin_bit_cast(w_half4_t, lo), bhi = __builtin_bit_cast(w_half4_t, hi);
-#pragma unroll
-          for (int n = 0; n < NH4; ++n) {
-            oq[2 * wd][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], blo, oq[2 * wd][n], 0, 0, 0);
-            oq[2 * wd + 1][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], bhi, oq[2 * wd + 1][n], 0, 0, 0);
-          }
+        for (int n = 0; n < NH4; ++n) {
+          const w_half4_t aop = *reinterpret_cast<const w_half4_t*>(&wp16[(4 * n + (lane & 3)) * 64 + 4 * kq]);
+          oq[0][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, blo, oq[0][n], 0, 0, 0);
+          oq[1][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bhi, oq[1][n], 0, 0, 0);
         }
       }
     } else {
@@ -433,11 +459,22 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   }
 
   if constexpr (!VQ) {
+    // ---- every lane holds its two channels, complete
 #pragma unroll
-    for (int h = 0; h < NH; ++h)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[h][e] = oq[e][h / 4][h % 4];
-  }
+    for (int h = 0; h < NH; ++h) {
+      if (h < r) {
+        const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
+        float2 ov;
+        ov.x = oq[0][h / 4][h % 4];
+        ov.y = oq[1][h / 4][h % 4];
+        *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + slot) * D + 2 * lane]) = ov;
+        if (lane == 0) {
+          a.ws_ml[(bhq * a.n_partials + slot) * 2 + 0] = m_run[h] * 0.6931471805599453f;
+          a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h];
+        }
+      }
+    }
+  } else {
   // ---- sum the four lane groups; lanes 0..15 then hold channels 8*lane .. 8*lane+7
 #pragma unroll
   for (int h = 0; h < NH; ++h)
@@ -460,6 +497,7 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
         a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h];
       }
     }
+  }
   }
 }
 
