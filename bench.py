@@ -34,6 +34,8 @@ def parse():
                    help="untimed steps first (the device needs some 10 ms of load before its clocks settle)")
     p.add_argument("--workload", default="llama3_8b_32k")
     p.add_argument("--kind", default="inner", choices=["inner", "outer", "fp16"])
+    p.add_argument("--context", type=int, default=None, metavar="N",
+                   help="override the workload's context length (same shape otherwise); the result then names it")
     p.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="code width (default: the workload's)")
     p.add_argument("--v-bits", type=int, default=0, choices=[0, 2, 3, 4],
                    help="width of the value codes when it differs from the keys' (0: the same)")
@@ -374,6 +376,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = wl.WORKLOADS[args.workload]
+    if args.context is not None:
+        w = w.with_(n_tokens=args.context, name=f"{w.name}@{args.context}")
     modes = {"sym": iq.SYM, "asym": iq.ASYM, "hybrid": iq.HYBRID}
     if args.bits:
         w = w.with_(bits=args.bits)

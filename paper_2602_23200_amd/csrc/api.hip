@@ -389,7 +389,12 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
                              : fused_kind == 2 ? attention_fp16_waves_per_cu(a)
                                                : attention_outer_waves_per_cu(a));
     const long long n_tiles = ceil_div(n_both, 64);
-    const long long per_head = slots / ((long long)c.batch * c.n_kv_heads);
+    long long per_head = slots / ((long long)c.batch * c.n_kv_heads);
+    // Short contexts: with fewer than about four tiles per wavefront, a launch of half as many
+    // wavefronts (one per SIMD instead of two) is the faster one -- every wavefront pays its query
+    // set-up once, and the launch itself costs time per wavefront (measured on the 32-head 4k-token
+    // configuration: 17.8 -> 14.3 us per step; the two meet at four tiles per wavefront).
+    if (fused_kind == 1 && n_tiles < 4 * per_head && per_head >= 8) per_head /= 2;
     // Window chunk length: 64 tokens when the wavefront slots are all needed for tiles (long
     // contexts: a chunk then hides behind the tile work), shorter when slots are to spare and the
     // window chunk would be the longest wavefront of the launch.  Costs in units of one tile of

@@ -145,9 +145,9 @@ struct TileRegs {
 // Tiles' worth of time a window chunk of `len` tokens costs the wavefront that carries it.  The
 // chunk runs at the lowest issue priority next to a partner that is busy about three quarters of
 // the time, so its wall time is several times its own instruction count; the slope is the one that
-// balances the launch best when swept (8 to 11 per 64 tokens: 11 on the 32k-token G = 32
-// configuration, 8 on the 8k x 32 G = 64 one, each 2 to 4 % better than the other's value).
-__host__ __device__ inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 8 : 11) * len / 64); }
+// balances the launch best when swept (3 to 11 per 64 tokens: flat between 5 and 11 on the 32k-token
+// G = 32 configuration, best at 9; best at 5 on the 8k x 32 G = 64 one, 6 % better than at 11).
+__host__ __device__ inline int window_cost(long long len, int group) { return (int)(2 + (group == 64 ? 5 : 9) * len / 64); }
 
 // KB, VB: widths of the key and value codes.  ZK: the key zero-point array exists (the key mode is not
 // symmetric-only).  ZV: 0 = no value zero-point array; 1 = zero-points read densely, one tile ahead with
@@ -238,6 +238,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // A wavefront without a tile (a launch with more wavefronts than tiles gives the window chunks
   // wavefronts of their own) skips all of the tile machinery, query tables included.
+  float part_m[NH], part_l[NH];
+  float2 part_o[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) { part_m[h] = -INFINITY; part_l[h] = 0.f; part_o[h] = float2{0.f, 0.f}; }   // (an empty partial)
   if (t1 > t0) {
   // ---- per-(b, hk) base pointers
   const long long slab = kPagedStore ? 0 : bh * a.capacity;             // first store row of (b, hk); paged: see below
@@ -330,11 +334,16 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ---- the query loads go out first (the set-up below waits for them), the first tile's loads
   // right behind them: those overlap the query set-up
   u32x4 q_raw[NH4];
+  float4_t q_fac[NH4][2];                              // per-channel query factors, when given
 #pragma unroll
   for (int rnd = 0; rnd < NH4; ++rnd) {
     const int h = (rnd * 64 + lane) / (D / 8), c0 = 8 * ((rnd * 64 + lane) % (D / 8));
     q_raw[rnd] = u32x4{0u, 0u, 0u, 0u};
     if (h < r) q_raw[rnd] = *reinterpret_cast<const u32x4*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + c0);
+    if (a.q_scale) {
+      q_fac[rnd][0] = *reinterpret_cast<const float4_t*>(a.q_scale + hk * D + c0);
+      q_fac[rnd][1] = *reinterpret_cast<const float4_t*>(a.q_scale + hk * D + c0 + 4);
+    }
   }
   Regs bufA, bufB;
   if (t1 > t0) load_tile(t0, bufA);
@@ -353,7 +362,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (e & 1) ? (rw[e / 2] >> 16) : (rw[e / 2] & 0xffffu);
       qv[e] = __half2float(__ushort_as_half((unsigned short)hb));
-      if (a.q_scale) qv[e] = __half2float(scaled_half(qv[e], a.q_scale[hk * D + c0 + e]));
+      if (a.q_scale) qv[e] = __half2float(scaled_half(qv[e], q_fac[rnd][e / 4][e % 4]));
       part += qv[e];
       mx = __builtin_fmaxf(mx, __builtin_fabsf(qv[e]));
     }
@@ -684,38 +693,34 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
 
-  // ---- partial (m, l, o) of every real head
-  const int slot = s_idx;
+  // ---- partial (m, l, o) of every real head, kept in registers over the window pass
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
-    if (h < r) {
-      const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
-      float2 ov;
-      ov.x = o[h][0] * 65536.0f;                       // 2^16 undoes the operand factors of the value pass
-      ov.y = o[h][1] * 65536.0f;
-      *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + slot) * D + 2 * lane]) = ov;
-      if (lane == 0) {
-        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 0] = m_run[h] * kLn2;
-        a.ws_ml[(bhq * a.n_partials + slot) * 2 + 1] = l_run[h] * 65536.0f;
-      }
-    }
+    part_o[h].x = o[h][0] * 65536.0f;                  // 2^16 undoes the operand factors of the value pass
+    part_o[h].y = o[h][1] * 65536.0f;
+    part_m[h] = m_run[h] * kLn2;
+    part_l[h] = l_run[h] * 65536.0f;
   }
-  } else {
-    // ---- an empty partial
-    for (int h = 0; h < r; ++h) {
-      const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
-      *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + s_idx) * D + 2 * lane]) = float2{0.f, 0.f};
-      if (lane == 0) {
-        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 0] = -INFINITY;
-        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 1] = 0.f;
-      }
-    }
   }
 
   // ---- the window chunk of this wavefront, with a partial slot of its own
   if (s_idx < win.n_chunks) {
     __builtin_amdgcn_s_setprio(0);
     window_pass<NH4, KB, G, true, false, kPagedStore>(a, bh, win.na, win.b0, win.nb, s_idx, win.n_chunks, n_splits + s_idx);
+  }
+
+  // ---- the tile partial goes out last: nothing after these stores reuses their registers (which
+  // would have to wait for the stores to complete)
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    if (h < r) {
+      const long long bhq = (long long)b * a.n_q_heads + hk * r + h;
+      *reinterpret_cast<float2*>(&a.ws_o[(bhq * a.n_partials + s_idx) * D + 2 * lane]) = part_o[h];
+      if (lane == 0) {
+        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 0] = part_m[h];
+        a.ws_ml[(bhq * a.n_partials + s_idx) * 2 + 1] = part_l[h];
+      }
+    }
   }
 }
 

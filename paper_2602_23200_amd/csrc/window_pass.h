@@ -130,7 +130,6 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   constexpr int NH = NH4 * 4;
   constexpr int NG = D / G;
   constexpr int FPW = 32 / BITS;             // fields per 32-bit word
-  constexpr int WPG = G / FPW;               // words per key group
   constexpr int KVEC = D * BITS / 128;       // 16-byte pieces of a packed row
   constexpr uint32_t FMASK = (1u << BITS) - 1u;
   constexpr float HALFCODE = (float)(1 << (BITS - 1));
@@ -144,7 +143,6 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   const long long v1 = v0 + chunk_len < total ? v0 + chunk_len : total;
 
   __shared__ __attribute__((aligned(16))) _Float16 wq[NH][D];       // query, fp16 (exact)
-  __shared__ __attribute__((aligned(16))) float wqf[KQ ? D : 1][NH];   // the same values as fp32, head fastest
   __shared__ __attribute__((aligned(16))) float wqs[NG][NH];        // their sums over each key group
   __shared__ __attribute__((aligned(16))) float wp[VQ ? 64 : 1][NH];   // probabilities of the current 64 tokens
   // the same, rounded to fp16, as matrix operands: [head][token]
@@ -176,6 +174,21 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
   for (int e = 0; e < 2; ++e)
 #pragma unroll
     for (int n = 0; n < NH4; ++n) oq[e][n] = w_float4_t{0.f, 0.f, 0.f, 0.f};
+
+  // the query (and its per-channel factors, if any) first: what the step below waits for first
+  w_u32x4 q_raw[NH4];
+  w_float4_t q_fac[NH4][2];
+#pragma unroll
+  for (int rnd = 0; rnd < NH4; ++rnd) {
+    const int idx = rnd * 64 + lane;
+    const int h = idx / (D / 8), c0 = 8 * (idx % (D / 8));
+    q_raw[rnd] = w_u32x4{0u, 0u, 0u, 0u};
+    if (h < r) q_raw[rnd] = *reinterpret_cast<const w_u32x4*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + c0);
+    if (a.q_scale) {
+      q_fac[rnd][0] = *reinterpret_cast<const w_float4_t*>(a.q_scale + hk * D + c0);
+      q_fac[rnd][1] = *reinterpret_cast<const w_float4_t*>(a.q_scale + hk * D + c0 + 4);
+    }
+  }
 
   for (long long base = v0; base < v1; base += 64) {
     // ---- all loads of this step
@@ -264,16 +277,14 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
       for (int rnd = 0; rnd < NH4; ++rnd) {
         const int idx = rnd * 64 + lane;
         const int h = idx / (D / 8), c0 = 8 * (idx % (D / 8));
-        w_u32x4 raw = w_u32x4{0u, 0u, 0u, 0u};
-        if (h < r) raw = *reinterpret_cast<const w_u32x4*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + c0);
+        const w_u32x4 raw = q_raw[rnd];
         const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
         float part = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           float qv = (e & 1) ? window_half_hi(rw[e / 2]) : window_half_lo(rw[e / 2]);
-          if (a.q_scale) qv = __half2float(scaled_half(qv, a.q_scale[hk * D + c0 + e]));
+          if (a.q_scale) qv = __half2float(scaled_half(qv, q_fac[rnd][e / 4][e % 4]));
           wq[h][c0 + e] = (_Float16)qv;
-          if constexpr (KQ) wqf[c0 + e][h] = qv;
           part += qv;
         }
         if constexpr (KQ) {
@@ -288,15 +299,46 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
     }
     __syncthreads();
 
-    // ---- scores: lane = token.  fp16 rows go through the matrix cores: 4x4x4 blocks, B = four
-    // consecutive channels of the lane's row (8 bytes as loaded), A = the same channels of the four
-    // heads (from wq), the four results land in the lane that holds the token.  Lanes whose row is
-    // a packed one take part with whatever their registers hold and are overwritten below.
+    // ---- packed key rows (KQ): the stored fields take the place of the fp16 row, as the fp16
+    // integers they are (0x6400 | u is 1024 + u; minus 1024, exact), so that one pass through the
+    // matrix cores serves both kinds of row; the scale and zero-point of each group go on afterwards
+    // (Eq. hybrid_dequant: |S| * sum(q * field) + Zeff * sum(q), the fields taken as they are stored).
+    if (KQ && k_packed) {
+      uint32_t pk[KVEC * 4];
+#pragma unroll
+      for (int i = 0; i < KVEC; ++i) { pk[4 * i] = kreg[i].x; pk[4 * i + 1] = kreg[i].y; pk[4 * i + 2] = kreg[i].z; pk[4 * i + 3] = kreg[i].w; }
+      auto field = [&](int c) -> uint32_t {
+        if constexpr (BITS == 3)      // a plane of 2-bit low parts (D/16 words), then a plane of high bits (D/32 words)
+          return ((pk[c / 16] >> (2 * (c % 16))) & 3u) | (((pk[D / 16 + c / 32] >> (c % 32)) & 1u) << 2);
+        else
+          return (pk[c / FPW] >> ((c % FPW) * BITS)) & FMASK;
+      };
+      typedef _Float16 w_half2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        uint32_t wd[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int c = 8 * i + 2 * k;
+          const uint32_t both = field(c) | (field(c + 1) << 16) | 0x64006400u;
+          const w_half2_t u = __builtin_bit_cast(w_half2_t, both) - w_half2_t{(_Float16)1024.0f, (_Float16)1024.0f};
+          wd[k] = __builtin_bit_cast(uint32_t, u);
+        }
+        kreg[i] = w_u32x4{wd[0], wd[1], wd[2], wd[3]};
+      }
+    }
+
+    // ---- scores: lane = token, through the matrix cores: 4x4x4 blocks, B = four consecutive
+    // channels of the lane's row, A = the same channels of the four heads (from wq), the four
+    // results land in the lane that holds the token.  One accumulator per key group: independent
+    // chains, and what a packed row needs.
     float s[NH];
     {
-      w_float4_t sacc[NH4];
+      w_float4_t sacc[NH4][NG];
 #pragma unroll
-      for (int n = 0; n < NH4; ++n) sacc[n] = w_float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int n = 0; n < NH4; ++n)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) sacc[n][g] = w_float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
 #pragma unroll
@@ -304,72 +346,32 @@ __device__ __forceinline__ void window_pass(const AttnArgs& a, long long bh, lon
           w_u32x2 bw;
           bw.x = hf ? kreg[i].z : kreg[i].x;
           bw.y = hf ? kreg[i].w : kreg[i].y;
-          w_half4_t bop = __builtin_bit_cast(w_half4_t, bw);
-          if (KQ && k_packed) bop = w_half4_t{(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};   // finite operands only
+          const w_half4_t bop = __builtin_bit_cast(w_half4_t, bw);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
             const w_half4_t aop = *reinterpret_cast<const w_half4_t*>(&wq[4 * n + (lane & 3)][8 * i + 4 * hf]);
-            sacc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, sacc[n], 0, 0, 0);
+            sacc[n][(8 * i) / G] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, sacc[n][(8 * i) / G], 0, 0, 0);
           }
         }
       }
 #pragma unroll
-      for (int n = 0; n < NH4; ++n) {
-        s[4 * n] = sacc[n].x; s[4 * n + 1] = sacc[n].y; s[4 * n + 2] = sacc[n].z; s[4 * n + 3] = sacc[n].w;
+      for (int h = 0; h < NH; ++h) {
+        s[h] = 0.f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) s[h] += sacc[h / 4][g][h % 4];
       }
-    }
-    if (KQ && k_packed) {
+      if (KQ && k_packed) {
 #pragma unroll
-      for (int h = 0; h < NH; ++h) s[h] = 0.f;
-      // a packed row, group by group (Eq. hybrid_dequant): |S| * sum(q * field) + Zeff * sum(q),
-      // the fields taken as they are stored
+        for (int h = 0; h < NH; ++h) s[h] = 0.f;
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        float acc[NH];
+        for (int g = 0; g < NG; ++g) {
+          const float sc = (g & 1) ? window_half_hi(ks[g / 2]) : window_half_lo(ks[g / 2]);
+          const float zp = (g & 1) ? window_half_hi(kz[g / 2]) : window_half_lo(kz[g / 2]);
+          const float S = fabsf(sc);
+          const float zeff = (__float_as_uint(sc) >> 31) ? zp : -S * HALFCODE;
 #pragma unroll
-        for (int h = 0; h < NH; ++h) acc[h] = 0.f;
-        if constexpr (BITS == 3) {
-          // a plane of 2-bit low parts (D/16 words), then a plane of high bits (D/32 words)
-#pragma unroll
-          for (int cc = 0; cc < G; ++cc) {
-            const int c = g * G + cc;
-            const int wl = c / 16, wh = D / 16 + c / 32;
-            const w_u32x4 pl = kreg[wl / 4], ph = kreg[wh / 4];
-            const uint32_t lo = (wl % 4) == 0 ? pl.x : (wl % 4) == 1 ? pl.y : (wl % 4) == 2 ? pl.z : pl.w;
-            const uint32_t hi = (wh % 4) == 0 ? ph.x : (wh % 4) == 1 ? ph.y : (wh % 4) == 2 ? ph.z : ph.w;
-            const float u = (float)(((lo >> (2 * (c % 16))) & 3u) | (((hi >> (c % 32)) & 1u) << 2));
-#pragma unroll
-            for (int n = 0; n < NH4; ++n) {
-              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[c][n * 4]);
-              acc[n * 4 + 0] += q4.x * u; acc[n * 4 + 1] += q4.y * u;
-              acc[n * 4 + 2] += q4.z * u; acc[n * 4 + 3] += q4.w * u;
-            }
-          }
-        } else {
-#pragma unroll
-        for (int wd = 0; wd < WPG; ++wd) {
-          const int wi = g * WPG + wd;
-          const w_u32x4 piece = kreg[wi / 4];
-          const uint32_t w = (wi % 4) == 0 ? piece.x : (wi % 4) == 1 ? piece.y : (wi % 4) == 2 ? piece.z : piece.w;
-#pragma unroll
-          for (int e = 0; e < FPW; ++e) {
-            const float u = (float)((w >> (e * BITS)) & FMASK);
-            const int c = wi * FPW + e;
-#pragma unroll
-            for (int n = 0; n < NH4; ++n) {
-              const w_float4_t q4 = *reinterpret_cast<const w_float4_t*>(&wqf[c][n * 4]);
-              acc[n * 4 + 0] += q4.x * u; acc[n * 4 + 1] += q4.y * u;
-              acc[n * 4 + 2] += q4.z * u; acc[n * 4 + 3] += q4.w * u;
-            }
-          }
+          for (int h = 0; h < NH; ++h) s[h] += S * sacc[h / 4][g][h % 4] + zeff * wqs[g][h];
         }
-        }
-        const float sc = (g & 1) ? window_half_hi(ks[g / 2]) : window_half_lo(ks[g / 2]);
-        const float zp = (g & 1) ? window_half_hi(kz[g / 2]) : window_half_lo(kz[g / 2]);
-        const float S = fabsf(sc);
-        const float zeff = (__float_as_uint(sc) >> 31) ? zp : -S * HALFCODE;
-#pragma unroll
-        for (int h = 0; h < NH; ++h) s[h] += S * acc[h] + zeff * wqs[g][h];
       }
     }
     __syncthreads();
