@@ -395,12 +395,9 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
     // set-up once, and the launch itself costs time per wavefront (measured on the 32-head 4k-token
     // configuration: 17.8 -> 14.3 us per step; the two meet at four tiles per wavefront).
     if (fused_kind == 1 && n_tiles < 4 * per_head && per_head >= 8) per_head /= 2;
-    // Window chunk length: 64 tokens when the wavefront slots are all needed for tiles (long
-    // contexts: a chunk then hides behind the tile work), shorter when slots are to spare and the
-    // window chunk would be the longest wavefront of the launch.  Costs in units of one tile of
-    // one wavefront: a chunk of L tokens about 4 + 14 L / 64.
+    // Window chunk length and the number of plain wavefronts.
     long long best_len = kWindowChunk, best_cost = -1, best_plain = 1;
-    for (long long len = kWindowChunk; len >= kWindowChunkMin; len /= 2) {
+    auto plain_for = [&](long long len) {
       const long long nw = ceil_div(win_tokens, len);
       long long plain = per_head - nw;
       if (plain > n_tiles) plain = n_tiles;
@@ -408,10 +405,32 @@ static int attention_impl(const innerq_config_t* cfg, const innerq_cache_t* cach
       // that carry a window chunk count as splits too
       const long long most = fused_kind == 1 ? split_cap(c) - nw : split_cap(c);
       if (plain > most) plain = most;
-      if (plain < 1) plain = 1;
-      const long long tile_cost = ceil_div(n_tiles, plain) * 8, win_cost = nw ? 32 + 14 * len / 8 : 0;   // x 8
-      const long long cost = tile_cost > win_cost ? tile_cost : win_cost;
-      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_len = len; best_plain = plain; }
+      return plain < 1 ? 1 : plain;
+    };
+    if (fused_kind == 1) {
+      // Inner kernel, as measured (a window chunk costs its wavefront about as much whatever its
+      // length, so short chunks pay only where wavefront slots go begging): 16 tokens while the
+      // whole launch fills at most a quarter of the SIMDs (4-head 512-token configuration: 10.4 us
+      // per step against 10.8 at 64); 32 tokens for short contexts on a busy chip (8 x 8 heads at 2k
+      // tokens: 12.5 us against 13.0 at 64 and 14.1 at 16); 64 tokens from about 3k tokens on
+      // (32 heads at 4k tokens: 13.4 us against 14.1 at 32 and 15.0 at 16) and wherever the slots
+      // are all needed for tiles.
+      const long long simds = (long long)compute_units() * 4;
+      const long long waves16 = (long long)c.batch * c.n_kv_heads * (plain_for(kWindowChunkMin) + ceil_div(win_tokens, kWindowChunkMin));
+      best_len = waves16 * 4 <= simds ? kWindowChunkMin : (n_tiles < 48 ? 32 : kWindowChunk);
+      best_plain = plain_for(best_len);
+    } else {
+      // Comparison kernels: 64 tokens when the wavefront slots are all needed for tiles (long
+      // contexts: a chunk then hides behind the tile work), shorter when slots are to spare and the
+      // window chunk would be the longest wavefront of the launch.  Costs in units of one tile of
+      // one wavefront: a chunk of L tokens about 4 + 14 L / 64.
+      for (long long len = kWindowChunk; len >= kWindowChunkMin; len /= 2) {
+        const long long nw = ceil_div(win_tokens, len);
+        const long long plain = plain_for(len);
+        const long long tile_cost = ceil_div(n_tiles, plain) * 8, win_cost = nw ? 32 + 14 * len / 8 : 0;   // x 8
+        const long long cost = tile_cost > win_cost ? tile_cost : win_cost;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_len = len; best_plain = plain; }
+      }
     }
     win_chunk_len = (int)best_len;
     const long long n_win_chunks = ceil_div(win_tokens, best_len);
