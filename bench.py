@@ -586,7 +586,8 @@ def main():
     # measured with (a hash); it is reported only while those sources are unchanged, else null.
     traffic, traffic_note = None, "this workload and kernel were not profiled"
     prof_md = os.path.join(ROOT, "profiles", f"attention_{args.kind}_{w.name}_hbm_traffic.md")
-    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits or args.v_bits):
+    if os.path.exists(prof_md) and not (args.k_mode or args.v_mode or args.bits or args.v_bits or args.paged
+                                        or args.sparse_zeros or args.asym_frac is not None):
         import re
         text = open(prof_md).read()
         m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", text, re.M)
