@@ -5,14 +5,19 @@
 // Same skeleton as the inner-grouped and fp16 kernels (one wavefront per token range, 64-token
 // tiles, register prefetch of the next tile, window wavefronts in the same launch, same merge), and
 // the multiply-accumulates run on the same 4x4x4 fp16 matrix instructions.  What differs is forced
-// by the grouping.  Along the inner dimension of q.K^T every channel of a key row has its own scale
-// and zero-point, and along the inner dimension of p.V every token has its own: nothing factors out
-// of an inner sum, so every element is dequantised (Eq. asym_dequant) to fp16 before it meets the
-// matrix cores.  And the packing runs across the inner dimension instead of along it (a key word
-// holds 16 tokens of ONE channel, a value word 16 channels of ONE token), so the fields of one inner
-// sum never sit in one lane: the dequantised keys go through an LDS tile to reach the
-// one-token-per-lane score pass, the value rows through an LDS staging area to reach the
-// channel-per-lane value pass.
+// by the grouping.  The packing runs across the inner dimension instead of along it (a key word
+// holds 16 tokens of ONE channel, a value word 16 channels of ONE token), while every operand layout
+// of the matrix instructions gives a lane consecutive indices of the inner dimension: the fields of
+// one inner sum never sit in one lane, so every element has to be taken out of its word and moved --
+// the keys through an LDS tile to reach the one-token-per-lane score pass, the value rows through an
+// LDS staging area to reach the channel-per-lane value pass -- at one vector instruction or more per
+// element.  The inner-grouped kernel masks two fields in place per instruction and moves nothing.
+// The scales themselves could be kept out of the element loop here too (a group's scale depends on
+// the summed index, so it can be folded into the OTHER operand once per group: a query table
+// q_c * S_{c,T} per token group, weight tables p_j * S_{j,g} per channel group, the zero-points as one
+// constant per group); that would replace the subtract and the multiply-add below (two of the four to
+// five instructions per pair of elements) by table set-up per tile, and leave the extraction and the
+// move.  Not built: the elements are dequantised (Eq. asym_dequant) to fp16 on their way.
 // Dequantisation costs two vector instructions per element: a field moved to mantissa bits 8..9 (6..9
 // for 4-bit codes) of an fp16 number with a fixed exponent reads as bias + u (bias 4, resp. 16), two
 // fields per 32-bit instruction; a packed subtract takes the bias off (exactly) and one packed fp16
