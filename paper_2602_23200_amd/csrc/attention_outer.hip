@@ -4,27 +4,25 @@
 //
 // Same skeleton as the inner-grouped and fp16 kernels (one wavefront per token range, 64-token
 // tiles, register prefetch of the next tile, window wavefronts in the same launch, same merge), and
-// the multiply-accumulates run on the same 4x4x4 fp16 matrix instructions.  What differs is forced
-// by the grouping.  The packing runs across the inner dimension instead of along it (a key word
-// holds 16 tokens of ONE channel, a value word 16 channels of ONE token), while every operand layout
-// of the matrix instructions gives a lane consecutive indices of the inner dimension: the fields of
-// one inner sum never sit in one lane, so every element has to be taken out of its word and moved --
-// the keys through an LDS tile to reach the one-token-per-lane score pass, the value rows through an
-// LDS staging area to reach the channel-per-lane value pass -- at one vector instruction or more per
-// element.  The inner-grouped kernel masks two fields in place per instruction and moves nothing.
-// The scales themselves could be kept out of the element loop here too (a group's scale depends on
-// the summed index, so it can be folded into the OTHER operand once per group: a query table
-// q_c * S_{c,T} per token group, weight tables p_j * S_{j,g} per channel group, the zero-points as one
-// constant per group); that would replace the subtract and the multiply-add below (two of the four to
-// five instructions per pair of elements) by table set-up per tile, and leave the extraction and the
-// move.  Not built: the elements are dequantised (Eq. asym_dequant) to fp16 on their way.
-// Dequantisation costs two vector instructions per element: a field moved to mantissa bits 8..9 (6..9
-// for 4-bit codes) of an fp16 number with a fixed exponent reads as bias + u (bias 4, resp. 16), two
-// fields per 32-bit instruction; a packed subtract takes the bias off (exactly) and one packed fp16
-// fused multiply-add forms S * u + Zeff for both, rounded once: the correctly rounded fp16 value of
-// the dequantised element.  (Folding the bias into the constant, S * (bias + u) + (Zeff - bias * S),
-// saves the subtract but rounds a constant several times larger than the element: 1e-2 on the
-// output with heavy-tailed keys, measured.)
+// built the same way as the inner-grouped kernel: the stored fields go to the 4x4x4 fp16 matrix
+// instructions as they are, masked in place (a field inside bits 0..10 of a 16-bit half reads as
+// field * 2^position * 2^-24), and scales and zero-points stay out of the element loop.  With outer
+// grouping a group's scale depends on the index that is summed over, so it cannot be applied to the
+// finished inner sum; it is folded into the OTHER operand instead, once per group:
+//     q . K^[j]        = sum_c (q_c S_{c,T}) u[j][c]  +  sum_c q_c Zeff_{c,T}      (T: token group of j)
+//     sum_j p_j V^[j][c] = sum_j (p_j S_{j,g}) u[j][c]  +  sum_j p_j Zeff_{j,g}    (g: channel group of c)
+// i.e. a query table per token group and a weight table per channel group, rebuilt for every tile, and the
+// zero-point terms as constants per group, summed on the matrix cores too.  (u = stored field, Zeff = Z for
+// an asymmetric group and -2^(b-1) |S| for a symmetric one: Eq. hybrid_dequant.)
+// What the grouping still forces, and the inner-grouped kernel does not pay:
+//   * the tables themselves: products rounded to fp16 (the query table in two pieces, or the rounding of a
+//     large channel's entry shows at 1e-3 on heavy-tailed keys), per-tile normalising shifts so that they
+//     stay in fp16's normal range, their way through LDS, and twice the matrix instructions on the keys;
+//   * the packing runs ACROSS the inner dimension (a key word holds 16 tokens of ONE channel, a value word
+//     16 channels of ONE token) while every operand layout of the matrix instructions gives a lane
+//     consecutive indices of the inner dimension: the key fields go through an LDS tile to reach the
+//     one-token-per-lane score pass, and the value fields of two rows are put side by side in a register
+//     so that one AND leaves one channel of two tokens.
 #include "innerq_dev.h"
 #include "window_pass.h"
 
@@ -61,35 +59,48 @@ struct OuterRegs {
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 
-// Two b-bit fields (one in each 16-bit half of w, at bit `at` of its half) as the fp16 pair (u, u'):
-// the field lands on the top mantissa bits under a fixed exponent, which reads as bias + u.
-template <int BITS>
-__device__ __forceinline__ half2_t fields_as_half2(uint32_t w, int at) {
-  constexpr int TOP = 10 - BITS;                           // first mantissa bit the field occupies
-  constexpr uint32_t MASK = (((1u << BITS) - 1u) << TOP) * 0x00010001u;
-  constexpr uint32_t EXPO = (BITS == 2 ? 0x4400u : 0x4C00u) * 0x00010001u;    // 4.0 resp. 16.0
-  constexpr _Float16 BIAS = BITS == 2 ? (_Float16)4.0f : (_Float16)16.0f;
-  const uint32_t moved = at < TOP ? w << (TOP - at) : w >> (at - TOP);
-  return __builtin_bit_cast(half2_t, (moved & MASK) | EXPO) - half2_t{BIAS, BIAS};
-}
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
-// (|S|, Zeff) of one group as an fp16 pair; Zeff = Z for an asymmetric group (scale sign bit set),
-// -2^(b-1) |S| for a symmetric one (Eq. hybrid_dequant).
-template <int BITS, bool HASZ>
-__device__ __forceinline__ half2_t scale_and_offset(float sc, float zp) {
-  const float S = fabsf(sc);
-  float z = -S * (float)(1 << (BITS - 1));
-  if constexpr (HASZ) z = (__float_as_uint(sc) >> 31) ? zp : z;
-  half2_t r;
-  r[0] = (_Float16)S;
-  r[1] = (_Float16)z;
-  return r;
+// A b-bit field masked in place inside a 16-bit half reads, as fp16, as field * 2^(bit position) * 2^-24
+// as long as it lies within bits 0..10 (the mantissa and the lowest exponent bit: the step from the
+// denormals to the first binade keeps the spacing).  Fields above that are taken from a copy of the word
+// shifted down by SH.  f = index of the field inside its half.
+template <int BITS>
+struct InPlace {
+  static constexpr int HALF = 16 / BITS;
+  static constexpr int SH = BITS == 2 ? 10 : 8;
+  static constexpr int NDIRECT = BITS == 2 ? 5 : 2;
+  static __host__ __device__ constexpr int pos(int f) { return f < NDIRECT ? f : f - NDIRECT; }
+  static __host__ __device__ constexpr uint32_t mask(int f) {
+    return (uint32_t)(((1u << BITS) - 1u) * 0x00010001u) << (BITS * pos(f));
+  }
+  // 2^24 / 2^(bit position): what brings the masked field back to its value
+  static __host__ __device__ constexpr float undo(int f) { return (float)(1 << (24 - BITS * pos(f))); }
+};
+
+__device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+__device__ __forceinline__ uint32_t as_u32(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
+
+// Power of two, as an fp16 pair, that brings the largest of the given fp16 magnitudes (bit patterns with
+// the sign cleared, two per word; wave-wide) below 1, and its exponent: the scales of a tile are folded
+// into the other operand of the products in that normalised form, so that the folded tables use the
+// normal range of fp16 whatever the magnitude of the cache.
+__device__ __forceinline__ int tile_shift(uint32_t magnitudes) {
+  const uint32_t m = magnitudes & 0xffffu, n = magnitudes >> 16;
+  const int top = (int)wave_max_o((float)(m > n ? m : n));       // (fp16 magnitudes order like integers)
+  const int sh = 14 - (top >> 10);                                // value < 2^(biased exponent - 14)
+  return sh < -14 ? -14 : sh;                                     // (at most 14: 2^sh is an fp16 number either way)
+}
+__device__ __forceinline__ half2_t pow2_half2(int e) {            // -14 <= e <= 15
+  return as_half2((uint32_t)((15 + e) << 10) * 0x00010001u);
 }
 
 template <int BITS, int G, int NH4, bool ZK, bool ZV>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NH4 == 1 ? 2 : 1, 2)))
 attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   using Regs = OuterRegs<BITS, G>;
+  using IP = InPlace<BITS>;
   constexpr int NH = NH4 * 4;
   constexpr int GPT = Regs::GPT, KC = Regs::KC, VC = Regs::VC, NG = Regs::NG;
   constexpr int FPW = 32 / BITS;
@@ -97,6 +108,17 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   constexpr int WPG = G / FPW;                         // words per channel of one key group
   constexpr int ROWB = D * BITS / 8;
   constexpr int ROWW = ROWB / 4;                       // words of one packed value row
+  constexpr int QROW = D + 8, AROW = 64 + 8;           // padded rows of the folded query tables (halves)
+  constexpr float kLevel = (float)(1 << (BITS - 1));   // symmetric zero-point: -2^(b-1) |S|  (Eq. hybrid_dequant)
+  // The fields enter the products as stored (0 .. 2^b - 1), so the rounding error of a folded table entry
+  // would be multiplied by up to 2^b - 1.  Taking the middle of the field range out of the zero-point term
+  // with the ROUNDED table entries,  S u + Zeff = S (u - kMid) + (Zeff + kMid S),  leaves each entry's
+  // error multiplied by |u - kMid| <= kMid only, and the explicit constant small.
+  constexpr float kMid = (float)((1 << BITS) - 1) * 0.5f;
+  // LDS operands are asked for well ahead of their use where the registers allow it (four heads, 2-bit
+  // codes: the measured configuration); the other instances read step by step
+  constexpr bool kAhead = NH4 == 1 && BITS == 2;
+  constexpr float kSlack = 6.0f;                       // scores may exceed the reference level by this (log2)
 
   const int lane = threadIdx.x;
   const long long bh = blockIdx.y;
@@ -113,21 +135,43 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   const int t0 = s_idx * base_t + (s_idx < rem_t ? s_idx : rem_t);
   const int t1 = t0 + base_t + (s_idx < rem_t ? 1 : 0);
 
-  __shared__ __attribute__((aligned(16))) _Float16 qs[NH][D];           // query, fp16 (exact)
-  __shared__ __attribute__((aligned(16))) _Float16 kt[TILE][KROW];      // dequantised keys, token-major
-  // probabilities of the tile, rounded to fp16, as matrix operands: [token % 4][head][token / 4]
-  __shared__ __attribute__((aligned(16))) _Float16 wp16[4 * NH * 16];
-  __shared__ __attribute__((aligned(16))) uint32_t vcode[TILE][ROWW + 1];   // packed value rows (padded)
-  __shared__ __attribute__((aligned(16))) half2_t vsz[TILE][NG];        // (|S|, Zeff) of each value group
+  // folded operand tables of the current tile (see the header): per key token-group the query times the
+  // group's scales, and the lanes' pieces of the zero-point term; per value channel-group the softmax
+  // weights times the tokens' scales ([NG]: the weights themselves), and the tokens' zero-points
+  __shared__ __attribute__((aligned(16))) _Float16 qT[GPT][NH][QROW];   // q S, rounded to fp16 ...
+  __shared__ __attribute__((aligned(16))) _Float16 qL[GPT][NH][QROW];   // ... and what the rounding left (q S = qT + qL to 2^-22)
+  __shared__ __attribute__((aligned(16))) _Float16 aT[GPT][NH][AROW];
+  __shared__ __attribute__((aligned(16))) _Float16 kt[TILE][KROW];      // key fields (masked in place), token-major
+  // The value pass's tables reuse the key tile's memory: they are written after the score pass has read
+  // the tile (a workgroup is one wavefront, whose LDS operations complete in order).  With them the
+  // workgroup needs 25 KB, six to a compute unit; a tile of their own made it 27.3 KB, which the
+  // occupancy query still counts as six while only five fit (LDS is handed out in 512-byte pieces).
+  constexpr int kTablesHalves = (NG + 1) * 4 * NH * 16 + NG * 64;
+  static_assert(kTablesHalves * 2 + TILE * (ROWW + 1) * 4 <= TILE * KROW * 2, "the value pass's tables fit the key tile");
+  _Float16 (*pT)[4 * NH * 16] = reinterpret_cast<_Float16 (*)[4 * NH * 16]>(&kt[0][0]);        // [NG + 1][token % 4][head][token / 4]
+  _Float16 (*zT)[4 * 16] = reinterpret_cast<_Float16 (*)[4 * 16]>(&kt[0][0] + (NG + 1) * 4 * NH * 16);   // [NG][token % 4][token / 4]
+  uint32_t (*vcode)[ROWW + 1] = reinterpret_cast<uint32_t (*)[ROWW + 1]>(&kt[0][0] + kTablesHalves);   // packed value rows (padded)
 
-  for (int i = lane; i < NH * D; i += 64) {
-    const int h = i / D, c = i % D;
-    float qv = 0.f;
+  // ---- query: this lane's two channels of every head, each head scaled by a power of two into [1/4, 1/2)
+  half2_t qn[NH];
+  int qe[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    float q0 = 0.f, q1 = 0.f;
     if (h < r) {
-      const __half qh = a.q[((long long)b * a.n_q_heads + hk * r + h) * D + c];
-      qv = a.q_scale ? __half2float(scaled_half(__half2float(qh), a.q_scale[hk * D + c])) : __half2float(qh);
+      const uint32_t raw = *reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.n_q_heads + hk * r + h) * D + 2 * lane);
+      q0 = half_lo(raw);
+      q1 = half_hi(raw);
+      if (a.q_scale) {
+        q0 = __half2float(scaled_half(q0, a.q_scale[hk * D + 2 * lane]));
+        q1 = __half2float(scaled_half(q1, a.q_scale[hk * D + 2 * lane + 1]));
+      }
     }
-    qs[h][c] = (_Float16)qv;
+    const float mx = wave_max_o(fmaxf(fabsf(q0), fabsf(q1)));
+    const int e = mx > 0.f ? (int)((__float_as_uint(mx) >> 23) & 0xffu) - 127 + 2 : 0;
+    qe[h] = e;
+    const float f = pow2f(-e);
+    qn[h] = half2_t{(_Float16)(q0 * f), (_Float16)(q1 * f)};
   }
 
   const long long kgroups = a.capacity / G;
@@ -170,49 +214,184 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   };
 
   const float c_log2 = 0.08838834764831845f * 1.4426950408889634f;
-  // oq[e][n]: channel 8 cg + e of this lane, heads 4 n .. 4 n + 3, the tokens 4 k + tg of every tile
-  float m_run[NH], l_run[NH];
-  float4_t oq[8][NH4];
+  // ---- running softmax state and accumulators.  m_run is a reference level that is raised (with a
+  // wave-wide reduction and a rescale) only when a score exceeds it by more than kSlack.
+  // oq[c][n]: channel c of this lane's eight, heads 4 n .. 4 n + 3, over the tokens 4 k + tg, in units of
+  // the masked fields and of the running value shift; oz: the zero-point term of the lane's channel
+  // group; ol: the sum of the weights.
+  float m_run[NH];
+  float4_t oq[8][NH4], oz[NH4], ol[NH4];
 #pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    m_run[h] = -INFINITY;
-    l_run[h] = 0.f;
+  for (int h = 0; h < NH; ++h) m_run[h] = -INFINITY;
+#pragma unroll
+  for (int n = 0; n < NH4; ++n) {
+    oz[n] = float4_t{0.f, 0.f, 0.f, 0.f};
+    ol[n] = oz[n];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) oq[c][n] = oz[n];
   }
-#pragma unroll
-  for (int e = 0; e < 8; ++e)
-#pragma unroll
-    for (int n = 0; n < NH4; ++n) oq[e][n] = float4_t{0.f, 0.f, 0.f, 0.f};
+  int shv_run = 64;                                    // the values' scales enter as S * 2^shv_run (64: nothing yet)
   const int cg = lane & 15, tg = lane >> 4;
+  const int gt = lane / G;                             // key token-group of this lane's token (score pass)
+  const int gch = (8 * cg) / G;                        // value channel-group of this lane's channels (value pass)
+  const int ptok = (lane % FPW) % HALF;                // where this lane's token sits in its half-word
+  const float ftok = pow2f(24 - BITS * (ptok < IP::NDIRECT ? ptok : ptok - IP::NDIRECT));
+  const uint32_t sel16 = (cg & 1) ? 0x07060302u : 0x05040100u;   // 2-bit: which half of a row word holds this lane's channels
+  const u32x2 ones2 = {0x3C003C00u, 0x3C003C00u};
+  const half4_t ones = __builtin_bit_cast(half4_t, ones2);
+  const half4_t mids = {(_Float16)(-kMid), (_Float16)(-kMid), (_Float16)(-kMid), (_Float16)(-kMid)};
 
-  Regs cur, nxt;
-  if (t0 < t1) load_tile(t0, cur);
-  for (int tile = t0; tile < t1; ++tile) {
-    if (tile + 1 < t1) load_tile(tile + 1, nxt);       // in flight while this tile is computed
+  auto process = [&](const Regs& cur, int tile) {
     __syncthreads();                                   // previous tile's readers of the LDS tiles are done
 
-    // ---- dequantise this lane's two key channels of all 64 tokens into the token-major tile: a word
-    // holds 2 x HALF tokens of one channel, so one instruction handles tokens (p, HALF + p) of it
+    // ---- keys.  K^[j][c] = S_{c,T} u[j][c] + Zeff_{c,T} (T = token group), so
+    //   q . K^[j] = sum_c (q_c S_{c,T}) u[j][c]  +  sum_c q_c Zeff_{c,T}:
+    // the scales go into a query table per token group (this lane owns channels 2 lane, 2 lane + 1),
+    // the zero-point term is a constant per token group and head, summed over the lanes' pieces on the
+    // matrix cores.  Everything is scaled by 2^shk so that the tables stay in fp16's normal range.
+    uint32_t kmag = 0;
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
-      const uint32_t sp = cur.ks[gi], zp = ZK ? cur.kz[gi] : 0u;
-      const half2_t sz0 = scale_and_offset<BITS, ZK>(half_lo(sp), half_lo(zp));
-      const half2_t sz1 = scale_and_offset<BITS, ZK>(half_hi(sp), half_hi(zp));
-      const half2_t S0 = {sz0[0], sz0[0]}, Z0 = {sz0[1], sz0[1]}, S1 = {sz1[0], sz1[0]}, Z1 = {sz1[1], sz1[1]};
+      kmag = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, kmag),
+                                                                    __builtin_bit_cast(ushort2_t, cur.ks[gi] & 0x7fff7fffu)));
+      if constexpr (ZK)
+        kmag = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, kmag),
+                                                                      __builtin_bit_cast(ushort2_t, cur.kz[gi] & 0x7fff7fffu)));
+    }
+    const int shk = tile_shift(kmag);
+    const half2_t fk = pow2_half2(shk);
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+      const half2_t sn = as_half2(cur.ks[gi] & 0x7fff7fffu) * fk;
+      half2_t zn;
+      if constexpr (ZK) {
+        // the sign bit of a scale marks an asymmetric group, whose zero-point is stored; a symmetric
+        // group stores +0 there and has Zeff = -2^(b-1) S
+        const half2_t ssym = __builtin_elementwise_max(as_half2(cur.ks[gi]), half2_t{(_Float16)0, (_Float16)0}) * fk;
+        zn = __builtin_elementwise_fma(as_half2(cur.kz[gi]), fk, ssym * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)});
+      } else {
+        zn = sn * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)};
+      }
+      const half2_t zc = __builtin_elementwise_fma(sn, half2_t{(_Float16)kMid, (_Float16)kMid}, zn);   // Zeff + kMid S
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        // q S in two fp16 pieces: with one, the rounding of a large channel's entry (2^-12 of it, times
+        // the field) shows in the output at 1e-3 on heavy-tailed keys
+        const half2_t qs = qn[h] * sn;
+        const float l0 = __builtin_fmaf((float)qn[h][0], (float)sn[0], -(float)qs[0]);
+        const float l1 = __builtin_fmaf((float)qn[h][1], (float)sn[1], -(float)qs[1]);
+        *reinterpret_cast<uint32_t*>(&qT[gi][h][2 * lane]) = as_u32(qs);
+        *reinterpret_cast<uint32_t*>(&qL[gi][h][2 * lane]) = as_u32(half2_t{(_Float16)l0, (_Float16)l1});
+        // this lane's piece of sum_c q_c (Zeff_c + kMid S_c)
+        aT[gi][h][lane] = (_Float16)__builtin_amdgcn_fdot2(qn[h], zc, 0.f, false);
+      }
+      // the fields themselves, masked in place, into the token-major tile: a word holds 2 x HALF tokens of
+      // one channel, so one AND handles tokens (p, HALF + p) of it
 #pragma unroll
       for (int wd = 0; wd < WPG; ++wd) {
         const uint32_t w0 = cur.kc[gi][wd / 4][wd % 4], w1 = cur.kc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
+        const uint32_t w0s = w0 >> IP::SH, w1s = w1 >> IP::SH;
 #pragma unroll
         for (int p = 0; p < HALF; ++p) {
-          const half2_t x0 = __builtin_elementwise_fma(fields_as_half2<BITS>(w0, p * BITS), S0, Z0);   // channel 2 lane: tokens p, HALF + p
-          const half2_t x1 = __builtin_elementwise_fma(fields_as_half2<BITS>(w1, p * BITS), S1, Z1);   // channel 2 lane + 1
-          const uint32_t u0 = __builtin_bit_cast(uint32_t, x0), u1 = __builtin_bit_cast(uint32_t, x1);
+          const uint32_t u0 = (p < IP::NDIRECT ? w0 : w0s) & IP::mask(p);   // channel 2 lane: tokens p, HALF + p
+          const uint32_t u1 = (p < IP::NDIRECT ? w1 : w1s) & IP::mask(p);   // channel 2 lane + 1
           const int tok = gi * G + wd * FPW + p;
           *reinterpret_cast<uint32_t*>(&kt[tok][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x05040100u);          // low halves
           *reinterpret_cast<uint32_t*>(&kt[tok + HALF][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x07060302u);   // high halves
         }
       }
     }
-    // ---- stage this lane's packed value row and its group constants
+    // ---- values' scales: the shift that normalises this tile's, and the running one
+    uint32_t vmag = 0;
+#pragma unroll
+    for (int gp = 0; gp < (NG + 1) / 2; ++gp) {
+      vmag = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, vmag),
+                                                                    __builtin_bit_cast(ushort2_t, cur.vs[gp] & 0x7fff7fffu)));
+      if constexpr (ZV)
+        vmag = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, vmag),
+                                                                      __builtin_bit_cast(ushort2_t, cur.vz[gp] & 0x7fff7fffu)));
+    }
+    const int shv_tile = tile_shift(vmag);
+    __syncthreads();
+
+    // ---- scores: lane = token (Eq. att:1), 4x4x4 blocks: B = four consecutive channels of the lane's
+    // row of fields, A = the same channels of four heads from the lane's token-group table
+    float s[NH];
+    {
+      // four independent chains: fields times the table and times its remainder, and the same two tables
+      // times the constant -kMid (the middle of the field range, taken with the rounded entries)
+      float4_t su[NH4], sl[NH4], sm[NH4], sn2[NH4], sz[NH4];
+#pragma unroll
+      for (int n = 0; n < NH4; ++n) {
+        su[n] = float4_t{0.f, 0.f, 0.f, 0.f};
+        sl[n] = su[n]; sm[n] = su[n]; sn2[n] = su[n]; sz[n] = su[n];
+      }
+      // The operands come from LDS in stages of STG steps (8 channels each), a stage's reads issued before
+      // the previous stage's matrix instructions: left to itself the compiler reads one or two steps ahead
+      // and the wavefront waits out an LDS round trip every few instructions.
+      constexpr int STG = kAhead ? 2 : 1, NST = D / 8 / STG;
+      u32x4 kvb[2][STG], qab[2][STG][NH4], qbb[2][STG][NH4], zab[64 / 8][NH4];
+      auto read_stage = [&](int st, int buf) {
+#pragma unroll
+        for (int j = 0; j < STG; ++j) {
+          const int i = st * STG + j;
+          kvb[buf][j] = *reinterpret_cast<const u32x4*>(&kt[lane][i * 8]);
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            qab[buf][j][n] = *reinterpret_cast<const u32x4*>(&qT[gt][4 * n + (lane & 3)][8 * i]);
+            qbb[buf][j][n] = *reinterpret_cast<const u32x4*>(&qL[gt][4 * n + (lane & 3)][8 * i]);
+          }
+        }
+      };
+      read_stage(0, 0);
+#pragma unroll
+      for (int st = 0; st < NST; ++st) {
+        if (st + 1 < NST) {
+          read_stage(st + 1, (st + 1) & 1);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 64 / 8; ++i)
+#pragma unroll
+            for (int n = 0; n < NH4; ++n) zab[i][n] = *reinterpret_cast<const u32x4*>(&aT[gt][4 * n + (lane & 3)][8 * i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < STG; ++j) {
+          const u32x4 kv = kvb[st & 1][j];
+          const half4_t k0 = __builtin_bit_cast(half4_t, u32x2{kv.x, kv.y}), k1 = __builtin_bit_cast(half4_t, u32x2{kv.z, kv.w});
+#pragma unroll
+          for (int n = 0; n < NH4; ++n) {
+            const u32x4 qa = qab[st & 1][j][n], qb = qbb[st & 1][j][n];
+            const half4_t a0 = __builtin_bit_cast(half4_t, u32x2{qa.x, qa.y}), a1 = __builtin_bit_cast(half4_t, u32x2{qa.z, qa.w});
+            const half4_t b0 = __builtin_bit_cast(half4_t, u32x2{qb.x, qb.y}), b1 = __builtin_bit_cast(half4_t, u32x2{qb.z, qb.w});
+            su[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(a0, k0, su[n], 0, 0, 0);
+            sl[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(b0, k0, sl[n], 0, 0, 0);
+            sm[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(a0, mids, sm[n], 0, 0, 0);
+            sn2[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(b0, mids, sn2[n], 0, 0, 0);
+            su[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(a1, k1, su[n], 0, 0, 0);
+            sl[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(b1, k1, sl[n], 0, 0, 0);
+            sm[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(a1, mids, sm[n], 0, 0, 0);
+            sn2[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(b1, mids, sn2[n], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = 0; i < 64 / 8; ++i) {
+#pragma unroll
+        for (int n = 0; n < NH4; ++n) {
+          const u32x4 za = zab[i][n];
+          sz[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, u32x2{za.x, za.y}), ones, sz[n], 0, 0, 0);
+          sz[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, u32x2{za.z, za.w}), ones, sz[n], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+        s[h] = __builtin_fmaf(su[h / 4][h % 4] + sl[h / 4][h % 4], ftok, (sm[h / 4][h % 4] + sn2[h / 4][h % 4]) + sz[h / 4][h % 4]) *
+               (c_log2 * pow2f(qe[h] - shk));
+    }
+    // ---- stage this lane's packed value row (in the key tile's memory, which the score pass has left),
+    // and ask for the rows the value pass will want: used after the softmax
 #pragma unroll
     for (int i = 0; i < VC; ++i) {
       vcode[lane][4 * i + 0] = cur.vc[i].x;
@@ -220,117 +399,160 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
       vcode[lane][4 * i + 2] = cur.vc[i].z;
       vcode[lane][4 * i + 3] = cur.vc[i].w;
     }
+    __syncthreads();
+    uint32_t vrow[4][4];
+    if constexpr (kAhead) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const uint32_t sp = cur.vs[g / 2], zp = ZV ? cur.vz[g / 2] : 0u;
-      vsz[lane][g] = scale_and_offset<BITS, ZV>((g & 1) ? half_hi(sp) : half_lo(sp), (g & 1) ? half_hi(zp) : half_lo(zp));
+      for (int kq = 0; kq < 4; ++kq)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vrow[kq][i] = vcode[16 * kq + 4 * i + tg][BITS == 2 ? cg / 2 : cg];
+    }
+    // ---- running softmax (Eq. att:2); the weights are rounded to fp16 for the matrix cores and the
+    // normaliser is the matrix cores' sum of the rounded weights
+    const bool valid = tile * TILE + lane <= last_row;
+    bool raise = false;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      s[h] = valid ? s[h] : -INFINITY;
+      raise |= s[h] > m_run[h] + kSlack;
+    }
+    const int shv_new = shv_tile < shv_run ? shv_tile : shv_run;
+    if (__builtin_amdgcn_ballot_w64(raise) != 0 || shv_new != shv_run) {
+      const float fshift = shv_run == 64 ? 0.f : pow2f(shv_new - shv_run);   // (nothing accumulated yet: any factor)
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const float m_new = fmaxf(m_run[h], wave_max_o(s[h]));
+        const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);        // 0 the first time
+        m_run[h] = m_new;
+        ol[h / 4][h % 4] *= alpha;
+        oz[h / 4][h % 4] *= alpha * fshift;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) oq[c][h / 4][h % 4] *= alpha * fshift;
+      }
+      shv_run = shv_new;
+    }
+    {
+      // sum_j p_j V^[j][c] = sum_j (p_j S_{j,g}) u[j][c] + sum_j p_j Zeff_{j,g}  (g = channel group of c):
+      // weight tables per channel group, and the tokens' zero-points as one more operand
+      const half2_t fv = pow2_half2(shv_run);
+      half2_t vsn[(NG + 1) / 2], vzn[(NG + 1) / 2];
+#pragma unroll
+      for (int gp = 0; gp < (NG + 1) / 2; ++gp) {
+        vsn[gp] = as_half2(cur.vs[gp] & 0x7fff7fffu) * fv;
+        if constexpr (ZV) {
+          const half2_t ssym = __builtin_elementwise_max(as_half2(cur.vs[gp]), half2_t{(_Float16)0, (_Float16)0}) * fv;
+          vzn[gp] = __builtin_elementwise_fma(as_half2(cur.vz[gp]), fv, ssym * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)});
+        } else {
+          vzn[gp] = vsn[gp] * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)};
+        }
+      }
+      const int slot = (lane & 3) * 16 + (lane >> 2);
+#pragma unroll
+      for (int gp = 0; gp < (NG + 1) / 2; ++gp)        // Zeff + kMid S (see kMid)
+        vzn[gp] = __builtin_elementwise_fma(vsn[gp], half2_t{(_Float16)kMid, (_Float16)kMid}, vzn[gp]);
+#pragma unroll
+      for (int g = 0; g < NG; ++g) zT[g][slot] = vzn[g / 2][g & 1];
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const _Float16 p16 = (_Float16)__builtin_amdgcn_exp2f(s[h] - m_run[h]);
+        const int idx = ((lane & 3) * NH + h) * 16 + (lane >> 2);
+        pT[NG][idx] = p16;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) pT[g][idx] = p16 * vsn[g / 2][g & 1];
+      }
     }
     __syncthreads();
-
-    // ---- scores: lane = token (Eq. att:1), 4x4x4 blocks: B = four consecutive channels of the lane's
-    // dequantised row, A = the same channels of four heads
-    float s[NH];
-    {
-      float4_t sacc[NH4];
+    // ---- values (Eq. att:3): lane = 8 channels (8 cg ..) of the tokens 4 k + tg.  Two rows' chunks side
+    // by side in the two halves of a register: one AND then leaves one channel of two tokens, half of a
+    // B operand (one channel of four tokens)
+    half4_t aops[4][NH4], aopls[4][NH4], zops[4];
+    auto read_weights = [&](int kq) {
 #pragma unroll
-      for (int n = 0; n < NH4; ++n) sacc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int n = 0; n < NH4; ++n) {
+        aops[kq][n] = *reinterpret_cast<const half4_t*>(&pT[gch][(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
+        aopls[kq][n] = *reinterpret_cast<const half4_t*>(&pT[NG][(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
+      }
+      zops[kq] = *reinterpret_cast<const half4_t*>(&zT[gch][tg * 16 + 4 * kq]);
+    };
+    if constexpr (kAhead) {
 #pragma unroll
-      for (int i = 0; i < D / 8; ++i) {
-        const u32x4 kv = *reinterpret_cast<const u32x4*>(&kt[lane][i * 8]);
+      for (int kq = 0; kq < 4; ++kq) read_weights(kq);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          u32x2 bw;
-          bw.x = hf ? kv.z : kv.x;
-          bw.y = hf ? kv.w : kv.y;
-          const half4_t bop = __builtin_bit_cast(half4_t, bw);
+    for (int kq = 0; kq < 4; ++kq) {
+      if constexpr (!kAhead) {
+        read_weights(kq);
 #pragma unroll
-          for (int n = 0; n < NH4; ++n) {
-            const half4_t aop = *reinterpret_cast<const half4_t*>(&qs[4 * n + (lane & 3)][8 * i + 4 * hf]);
-            sacc[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop, bop, sacc[n], 0, 0, 0);
-          }
-        }
+        for (int i = 0; i < 4; ++i) vrow[kq][i] = vcode[16 * kq + 4 * i + tg][BITS == 2 ? cg / 2 : cg];
+      }
+      const half4_t* aop = aops[kq];
+      const half4_t* aopl = aopls[kq];
+      const half4_t zop = zops[kq];
+      uint32_t src[2][8 / IP::HALF][2];                  // [direct | shifted][16-bit chunk][rows 0,1 | rows 2,3]
+      const uint32_t x0 = vrow[kq][0], x1 = vrow[kq][1], x2 = vrow[kq][2], x3 = vrow[kq][3];   // rows 16 kq + tg + 0, 4, 8, 12
+      if constexpr (BITS == 2) {
+        src[0][0][0] = __builtin_amdgcn_perm(x1, x0, sel16);
+        src[0][0][1] = __builtin_amdgcn_perm(x3, x2, sel16);
+      } else {
+        src[0][0][0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u);   // channels 0..3 of rows 0, 1
+        src[0][0][1] = __builtin_amdgcn_perm(x3, x2, 0x05040100u);
+        src[0][1][0] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);   // channels 4..7
+        src[0][1][1] = __builtin_amdgcn_perm(x3, x2, 0x07060302u);
+      }
+#pragma unroll
+      for (int ck = 0; ck < 8 / IP::HALF; ++ck)
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) src[1][ck][pr] = src[0][ck][pr] >> IP::SH;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int ck = c / IP::HALF, f = c % IP::HALF;
+        const int sh = f < IP::NDIRECT ? 0 : 1;
+        const u32x2 bw = {src[sh][ck][0] & IP::mask(f), src[sh][ck][1] & IP::mask(f)};
+        const half4_t bop = __builtin_bit_cast(half4_t, bw);
+#pragma unroll
+        for (int n = 0; n < NH4; ++n) oq[c][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], bop, oq[c][n], 0, 0, 0);
       }
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
-        s[4 * n] = sacc[n].x; s[4 * n + 1] = sacc[n].y; s[4 * n + 2] = sacc[n].z; s[4 * n + 3] = sacc[n].w;
+        oz[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aopl[n], zop, oz[n], 0, 0, 0);
+        oz[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], mids, oz[n], 0, 0, 0);       // - kMid * (weights times scales, as rounded)
+        ol[n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aopl[n], ones, ol[n], 0, 0, 0);
       }
     }
-    // ---- running softmax (Eq. att:2); the weights are rounded to fp16 for the matrix cores and the
-    // normaliser is formed from the rounded weights
-    const bool valid = tile * TILE + lane <= last_row;
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
-      const float sv = valid ? s[h] * c_log2 : -INFINITY;
-      const float m_new = fmaxf(m_run[h], wave_max_o(sv));
-      const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);
-      const _Float16 p16 = (_Float16)__builtin_amdgcn_exp2f(sv - m_new);
-      wp16[((lane & 3) * NH + h) * 16 + (lane >> 2)] = p16;
-      l_run[h] = l_run[h] * alpha + wave_sum_o((float)p16);
-      m_run[h] = m_new;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) oq[e][h / 4][h % 4] *= alpha;
+  };
+
+  // two register buffers in turn: the next tile's loads are in flight while this one is computed
+  {
+    Regs bufA, bufB;
+    if (t0 < t1) load_tile(t0, bufA);
+    int tile = t0;
+    while (tile + 1 < t1) {
+      load_tile(tile + 1, bufB);
+      process(bufA, tile);
+      if (tile + 2 < t1) load_tile(tile + 2, bufA);
+      process(bufB, tile + 1);
+      tile += 2;
     }
-    __syncthreads();
-    // ---- values (Eq. att:3): lane = 8 channels (8 cg ..) of the tokens 4 k + tg; every row chunk is
-    // dequantised to four fp16 pairs, then four rows give the B operands (one channel of four tokens)
-#pragma unroll
-    for (int kq = 0; kq < 4; ++kq) {
-      half4_t aop[NH4];
-#pragma unroll
-      for (int n = 0; n < NH4; ++n)
-        aop[n] = *reinterpret_cast<const half4_t*>(&wp16[(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
-      uint32_t x[4][4];                                  // [row][pair]: dequantised fp16 pairs
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int j = 4 * (4 * kq + i) + tg;
-        const half2_t sz = vsz[j][(8 * cg) / G];
-        const half2_t S = {sz[0], sz[0]}, Z = {sz[1], sz[1]};
-        if constexpr (BITS == 2) {
-          // 8 fields in 16 bits: low half = the chunk, high half = the chunk >> 2, so that pair e holds
-          // fields 2 e (low half) and 2 e + 1 (high half) at bit 4 e of their halves
-          const uint32_t c16 = (vcode[j][cg / 2] >> ((cg & 1) * 16)) & 0xffffu;
-          const uint32_t w = (c16 << 14) | c16;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            x[i][e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(fields_as_half2<2>(w, 4 * e), S, Z));
-        } else {
-          // 8 fields in 32 bits: pair e holds fields e (low half) and e + 4 (high half) at bit 4 e
-          const uint32_t w = vcode[j][cg];
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            x[i][e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(fields_as_half2<4>(w, 4 * e), S, Z));
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        u32x2 lo, hi;
-        lo.x = __builtin_amdgcn_perm(x[1][e], x[0][e], 0x05040100u);   // low halves of rows 0, 1
-        lo.y = __builtin_amdgcn_perm(x[3][e], x[2][e], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(x[1][e], x[0][e], 0x07060302u);   // high halves
-        hi.y = __builtin_amdgcn_perm(x[3][e], x[2][e], 0x07060302u);
-        const half4_t blo = __builtin_bit_cast(half4_t, lo), bhi = __builtin_bit_cast(half4_t, hi);
-        // channel of the low / high half of pair e (see the two packings above)
-        constexpr int STEP = BITS == 2 ? 1 : 4;
-        const int c_lo = BITS == 2 ? 2 * e : e, c_hi = c_lo + STEP;
-#pragma unroll
-        for (int n = 0; n < NH4; ++n) {
-          oq[c_lo][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], blo, oq[c_lo][n], 0, 0, 0);
-          oq[c_hi][n] = __builtin_amdgcn_mfma_f32_4x4x4f16(aop[n], bhi, oq[c_hi][n], 0, 0, 0);
-        }
-      }
-    }
-    cur = nxt;
+    if (tile < t1) process(bufA, tile);
   }
 
-  float o[NH][8];
+  // ---- partial result: undo the field positions and the value shift, add the zero-point term, and sum
+  // over the four token classes (lanes 16 apart)
+  const float fv_undo = shv_run == 64 ? 0.f : pow2f(-shv_run);
+  float o[NH][8], l_run[NH];
 #pragma unroll
-  for (int h = 0; h < NH; ++h)
+  for (int h = 0; h < NH; ++h) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      o[h][e] = oq[e][h / 4][h % 4];
-      o[h][e] += __shfl_xor(o[h][e], 16);
-      o[h][e] += __shfl_xor(o[h][e], 32);
+    for (int c = 0; c < 8; ++c) {
+      o[h][c] = __builtin_fmaf(oq[c][h / 4][h % 4], IP::undo(c % IP::HALF), oz[h / 4][h % 4]) * fv_undo;
+      o[h][c] += __shfl_xor(o[h][c], 16);
+      o[h][c] += __shfl_xor(o[h][c], 32);
     }
+    l_run[h] = ol[h / 4][h % 4];
+    l_run[h] += __shfl_xor(l_run[h], 16);
+    l_run[h] += __shfl_xor(l_run[h], 32);
+  }
   const int slot = s_idx;
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
@@ -379,15 +601,38 @@ bool attention_outer_supported(const AttnArgs& a) {
          a.capacity * D <= (1LL << 31) && !a.pages.table;
 }
 
+namespace {
+// Resident workgroups per compute unit of one instance: the runtime's answer, bounded by the LDS the
+// instance declares rounded up to the allocation granule (the runtime's answer was one too many for a
+// workgroup of 27 264 bytes: six counted, five resident, and the launch ran in two rounds).
+template <int BITS, int G, int NH4>
+int resident_outer() {
+  const auto kernel = attention_outer_kernel<BITS, G, NH4, true, true>;
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 64, 0) != hipSuccess || n <= 0) return 4;
+  hipFuncAttributes fa;
+  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) == hipSuccess && fa.sharedSizeBytes > 0) {
+    const size_t granule = 1024, lds_per_cu = 160 * 1024;
+    const int by_lds = (int)(lds_per_cu / (((fa.sharedSizeBytes + granule - 1) / granule) * granule));
+    if (by_lds >= 1 && by_lds < n) n = by_lds;
+  }
+  return n;
+}
+}  // namespace
+
 int attention_outer_waves_per_cu(const AttnArgs& a) {
-  // 64-thread groups, about 26 KB of LDS each: the LDS budget of a compute unit decides
-  (void)a;
-  static CachedInt c;
-  return c.get([] {
-    int n = 0;
-    const hipError_t e =
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attention_outer_kernel<2, 32, 1, true, true>, 64, 0);
-    return (e == hipSuccess && n > 0) ? n : 4;
+  // 64-thread groups, 22 to 33 KB of LDS each: the LDS budget of a compute unit decides; the instances
+  // for more than four heads per kv head also run one wavefront to a SIMD (registers)
+  static CachedInt c[2][2][2];
+  const int r = a.n_q_heads / a.n_kv_heads;
+  const bool b4 = a.bits == 4, g64 = a.group == 64, wide = r > 4;
+  return c[b4][g64][wide].get([&] {
+    if (b4) {
+      if (g64) return wide ? resident_outer<4, 64, 2>() : resident_outer<4, 64, 1>();
+      return wide ? resident_outer<4, 32, 2>() : resident_outer<4, 32, 1>();
+    }
+    if (g64) return wide ? resident_outer<2, 64, 2>() : resident_outer<2, 64, 1>();
+    return wide ? resident_outer<2, 32, 2>() : resident_outer<2, 32, 1>();
   });
 }
 
