@@ -213,9 +213,10 @@ def compare_kinds(torch, iq, hip, w, cfg, args, gen, inner_kernel_ms, stream):
     out = {"inner_kernel_ms": inner_kernel_ms,
            "paper_context": "the paper reports 2.7x over fp16 and 1.3x over outer grouping (KIVI-style) for its "
                             "CUDA kernels on an NVIDIA Jetson Xavier NX: other hardware, context only",
-           "outer_kernel_note": "the outer-grouped kernel dequantises every element to fp16 on its way to the matrix "
-                                "cores and does not fold the scales into the other operand: the inner/outer ratio is "
-                                "an upper bound on what the grouping alone costs"}
+           "outer_kernel_note": "the outer-grouped kernel is built like the inner-grouped one (stored fields masked in "
+                                "place as matrix operands, scales folded into the other operand once per group, "
+                                "zero-point terms as per-group constants): what separates the two is what the grouping "
+                                "forces (tables rebuilt per tile, the transposes)"}
     B, Hq, d = w.batch, w.n_q_heads, w.head_dim
     q = torch.randn((B, Hq, d), device="cuda", generator=gen).half()
     o = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")

@@ -138,19 +138,21 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   // folded operand tables of the current tile (see the header): per key token-group the query times the
   // group's scales, and the lanes' pieces of the zero-point term; per value channel-group the softmax
   // weights times the tokens' scales ([NG]: the weights themselves), and the tokens' zero-points
-  __shared__ __attribute__((aligned(16))) _Float16 qT[GPT][NH][QROW];   // q S, rounded to fp16 ...
-  __shared__ __attribute__((aligned(16))) _Float16 qL[GPT][NH][QROW];   // ... and what the rounding left (q S = qT + qL to 2^-22)
-  __shared__ __attribute__((aligned(16))) _Float16 aT[GPT][NH][AROW];
-  __shared__ __attribute__((aligned(16))) _Float16 kt[TILE][KROW];      // key fields (masked in place), token-major
-  // The value pass's tables reuse the key tile's memory: they are written after the score pass has read
-  // the tile (a workgroup is one wavefront, whose LDS operations complete in order).  With them the
-  // workgroup needs 25 KB, six to a compute unit; a tile of their own made it 27.3 KB, which the
-  // occupancy query still counts as six while only five fit (LDS is handed out in 512-byte pieces).
+  __shared__ __attribute__((aligned(16))) _Float16 qT[NH][QROW];        // q S of the current token group, rounded to fp16 ...
+  __shared__ __attribute__((aligned(16))) _Float16 qL[NH][QROW];        // ... and what the rounding left (q S = qT + qL to 2^-22)
+  __shared__ __attribute__((aligned(16))) _Float16 aT[NH][AROW];        // the lanes' pieces of the group's constant term
+  // One region serves as the key tile of a 32-token sub-pass (fields masked in place, token-major) and,
+  // once the score pass has read that, as the value pass's tables and packed rows (a workgroup is one
+  // wavefront, whose LDS operations complete in order).  14 to 20 KB per workgroup with the window
+  // pass's arrays: eight workgroups to a compute unit, two wavefronts to a SIMD.
+  constexpr int SUB = 32;                              // tokens per key sub-pass
   constexpr int kTablesHalves = (NG + 1) * 4 * NH * 16 + NG * 64;
-  static_assert(kTablesHalves * 2 + TILE * (ROWW + 1) * 4 <= TILE * KROW * 2, "the value pass's tables fit the key tile");
-  _Float16 (*pT)[4 * NH * 16] = reinterpret_cast<_Float16 (*)[4 * NH * 16]>(&kt[0][0]);        // [NG + 1][token % 4][head][token / 4]
-  _Float16 (*zT)[4 * 16] = reinterpret_cast<_Float16 (*)[4 * 16]>(&kt[0][0] + (NG + 1) * 4 * NH * 16);   // [NG][token % 4][token / 4]
-  uint32_t (*vcode)[ROWW + 1] = reinterpret_cast<uint32_t (*)[ROWW + 1]>(&kt[0][0] + kTablesHalves);   // packed value rows (padded)
+  constexpr int kKeyBytes = SUB * KROW * 2, kValueBytes = kTablesHalves * 2 + TILE * (ROWW + 1) * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char region[kKeyBytes > kValueBytes ? kKeyBytes : kValueBytes];
+  _Float16 (*kt)[KROW] = reinterpret_cast<_Float16 (*)[KROW]>(region);
+  _Float16 (*pT)[4 * NH * 16] = reinterpret_cast<_Float16 (*)[4 * NH * 16]>(region);           // [NG + 1][token % 4][head][token / 4]
+  _Float16 (*zT)[4 * 16] = reinterpret_cast<_Float16 (*)[4 * 16]>(region + (NG + 1) * 4 * NH * 16 * 2);   // [NG][token % 4][token / 4]
+  uint32_t (*vcode)[ROWW + 1] = reinterpret_cast<uint32_t (*)[ROWW + 1]>(region + kTablesHalves * 2);     // packed value rows (padded)
 
   // ---- query: this lane's two channels of every head, each head scaled by a power of two into [1/4, 1/2)
   half2_t qn[NH];
@@ -232,7 +234,6 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   }
   int shv_run = 64;                                    // the values' scales enter as S * 2^shv_run (64: nothing yet)
   const int cg = lane & 15, tg = lane >> 4;
-  const int gt = lane / G;                             // key token-group of this lane's token (score pass)
   const int gch = (8 * cg) / G;                        // value channel-group of this lane's channels (value pass)
   const int ptok = (lane % FPW) % HALF;                // where this lane's token sits in its half-word
   const float ftok = pow2f(24 - BITS * (ptok < IP::NDIRECT ? ptok : ptok - IP::NDIRECT));
@@ -249,6 +250,9 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
     // the scales go into a query table per token group (this lane owns channels 2 lane, 2 lane + 1),
     // the zero-point term is a constant per token group and head, summed over the lanes' pieces on the
     // matrix cores.  Everything is scaled by 2^shk so that the tables stay in fp16's normal range.
+    // The 64 tokens of the tile go through in two sub-passes of 32 (half the LDS for the token-major
+    // tile): in a sub-pass a lane takes one token and one half of the channels, and the two halves of a
+    // token's sum meet across lanes 32 apart.
     uint32_t kmag = 0;
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
@@ -260,47 +264,6 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
     }
     const int shk = tile_shift(kmag);
     const half2_t fk = pow2_half2(shk);
-#pragma unroll
-    for (int gi = 0; gi < GPT; ++gi) {
-      const half2_t sn = as_half2(cur.ks[gi] & 0x7fff7fffu) * fk;
-      half2_t zn;
-      if constexpr (ZK) {
-        // the sign bit of a scale marks an asymmetric group, whose zero-point is stored; a symmetric
-        // group stores +0 there and has Zeff = -2^(b-1) S
-        const half2_t ssym = __builtin_elementwise_max(as_half2(cur.ks[gi]), half2_t{(_Float16)0, (_Float16)0}) * fk;
-        zn = __builtin_elementwise_fma(as_half2(cur.kz[gi]), fk, ssym * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)});
-      } else {
-        zn = sn * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)};
-      }
-      const half2_t zc = __builtin_elementwise_fma(sn, half2_t{(_Float16)kMid, (_Float16)kMid}, zn);   // Zeff + kMid S
-#pragma unroll
-      for (int h = 0; h < NH; ++h) {
-        // q S in two fp16 pieces: with one, the rounding of a large channel's entry (2^-12 of it, times
-        // the field) shows in the output at 1e-3 on heavy-tailed keys
-        const half2_t qs = qn[h] * sn;
-        const float l0 = __builtin_fmaf((float)qn[h][0], (float)sn[0], -(float)qs[0]);
-        const float l1 = __builtin_fmaf((float)qn[h][1], (float)sn[1], -(float)qs[1]);
-        *reinterpret_cast<uint32_t*>(&qT[gi][h][2 * lane]) = as_u32(qs);
-        *reinterpret_cast<uint32_t*>(&qL[gi][h][2 * lane]) = as_u32(half2_t{(_Float16)l0, (_Float16)l1});
-        // this lane's piece of sum_c q_c (Zeff_c + kMid S_c)
-        aT[gi][h][lane] = (_Float16)__builtin_amdgcn_fdot2(qn[h], zc, 0.f, false);
-      }
-      // the fields themselves, masked in place, into the token-major tile: a word holds 2 x HALF tokens of
-      // one channel, so one AND handles tokens (p, HALF + p) of it
-#pragma unroll
-      for (int wd = 0; wd < WPG; ++wd) {
-        const uint32_t w0 = cur.kc[gi][wd / 4][wd % 4], w1 = cur.kc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
-        const uint32_t w0s = w0 >> IP::SH, w1s = w1 >> IP::SH;
-#pragma unroll
-        for (int p = 0; p < HALF; ++p) {
-          const uint32_t u0 = (p < IP::NDIRECT ? w0 : w0s) & IP::mask(p);   // channel 2 lane: tokens p, HALF + p
-          const uint32_t u1 = (p < IP::NDIRECT ? w1 : w1s) & IP::mask(p);   // channel 2 lane + 1
-          const int tok = gi * G + wd * FPW + p;
-          *reinterpret_cast<uint32_t*>(&kt[tok][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x05040100u);          // low halves
-          *reinterpret_cast<uint32_t*>(&kt[tok + HALF][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x07060302u);   // high halves
-        }
-      }
-    }
     // ---- values' scales: the shift that normalises this tile's, and the running one
     uint32_t vmag = 0;
 #pragma unroll
@@ -312,14 +275,61 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
                                                                       __builtin_bit_cast(ushort2_t, cur.vz[gp] & 0x7fff7fffu)));
     }
     const int shv_tile = tile_shift(vmag);
-    __syncthreads();
 
-    // ---- scores: lane = token (Eq. att:1), 4x4x4 blocks: B = four consecutive channels of the lane's
-    // row of fields, A = the same channels of four heads from the lane's token-group table
     float s[NH];
-    {
-      // four independent chains: fields times the table and times its remainder, and the same two tables
-      // times the constant -kMid (the middle of the field range, taken with the rounded entries)
+    const int tl = lane & (SUB - 1), chh = lane / SUB;   // sub-pass: this lane's token and half of the channels
+#pragma unroll
+    for (int sp = 0; sp < TILE / SUB; ++sp) {
+      const int gi = sp * SUB / G;                        // the sub-pass's token group (G = 64: one for both)
+      if (sp > 0) __syncthreads();                        // the first sub-pass has read the tile and the tables
+      if (G == SUB || sp == 0) {
+        const half2_t sn = as_half2(cur.ks[gi] & 0x7fff7fffu) * fk;
+        half2_t zn;
+        if constexpr (ZK) {
+          // the sign bit of a scale marks an asymmetric group, whose zero-point is stored; a symmetric
+          // group stores +0 there and has Zeff = -2^(b-1) S
+          const half2_t ssym = __builtin_elementwise_max(as_half2(cur.ks[gi]), half2_t{(_Float16)0, (_Float16)0}) * fk;
+          zn = __builtin_elementwise_fma(as_half2(cur.kz[gi]), fk, ssym * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)});
+        } else {
+          zn = sn * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)};
+        }
+        const half2_t zc = __builtin_elementwise_fma(sn, half2_t{(_Float16)kMid, (_Float16)kMid}, zn);   // Zeff + kMid S
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+          // q S in two fp16 pieces: with one, the rounding of a large channel's entry (2^-12 of it, times
+          // the field) shows in the output at 1e-3 on heavy-tailed keys
+          const half2_t qs = qn[h] * sn;
+          const float l0 = __builtin_fmaf((float)qn[h][0], (float)sn[0], -(float)qs[0]);
+          const float l1 = __builtin_fmaf((float)qn[h][1], (float)sn[1], -(float)qs[1]);
+          *reinterpret_cast<uint32_t*>(&qT[h][2 * lane]) = as_u32(qs);
+          *reinterpret_cast<uint32_t*>(&qL[h][2 * lane]) = as_u32(half2_t{(_Float16)l0, (_Float16)l1});
+          // this lane's piece of sum_c q_c (Zeff_c + kMid S_c)
+          aT[h][lane] = (_Float16)__builtin_amdgcn_fdot2(qn[h], zc, 0.f, false);
+        }
+      }
+      // the fields themselves, masked in place, into the token-major tile: a word holds 2 x HALF tokens of
+      // one channel, so one AND handles tokens (p, HALF + p) of it
+      constexpr int WPS = SUB / FPW;                      // words of one channel per sub-pass
+#pragma unroll
+      for (int ws = 0; ws < WPS; ++ws) {
+        const int wd = (sp * SUB - gi * G) / FPW + ws;    // word inside the group's run
+        const uint32_t w0 = cur.kc[gi][wd / 4][wd % 4], w1 = cur.kc[gi][(WPG + wd) / 4][(WPG + wd) % 4];
+        const uint32_t w0s = w0 >> IP::SH, w1s = w1 >> IP::SH;
+#pragma unroll
+        for (int p = 0; p < HALF; ++p) {
+          const uint32_t u0 = (p < IP::NDIRECT ? w0 : w0s) & IP::mask(p);   // channel 2 lane: tokens p, HALF + p
+          const uint32_t u1 = (p < IP::NDIRECT ? w1 : w1s) & IP::mask(p);   // channel 2 lane + 1
+          const int tok = ws * FPW + p;                   // token inside the sub-pass
+          *reinterpret_cast<uint32_t*>(&kt[tok][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x05040100u);          // low halves
+          *reinterpret_cast<uint32_t*>(&kt[tok + HALF][2 * lane]) = __builtin_amdgcn_perm(u1, u0, 0x07060302u);   // high halves
+        }
+      }
+      __syncthreads();
+
+      // ---- scores of the sub-pass (Eq. att:1), 4x4x4 blocks: B = four consecutive channels of the lane's
+      // row of fields, A = the same channels of four heads from the group's table.  Four independent
+      // chains: fields times the table and times its remainder, and the same two tables times the constant
+      // -kMid (the middle of the field range, taken with the rounded entries).
       float4_t su[NH4], sl[NH4], sm[NH4], sn2[NH4], sz[NH4];
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
@@ -329,17 +339,18 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
       // The operands come from LDS in stages of STG steps (8 channels each), a stage's reads issued before
       // the previous stage's matrix instructions: left to itself the compiler reads one or two steps ahead
       // and the wavefront waits out an LDS round trip every few instructions.
-      constexpr int STG = kAhead ? 2 : 1, NST = D / 8 / STG;
-      u32x4 kvb[2][STG], qab[2][STG][NH4], qbb[2][STG][NH4], zab[64 / 8][NH4];
+      constexpr int NSTEP = D / 2 / 8, NPIECE = 64 / 2 / 8;
+      constexpr int STG = kAhead ? 2 : 1, NST = NSTEP / STG;
+      u32x4 kvb[2][STG], qab[2][STG][NH4], qbb[2][STG][NH4], zab[NPIECE][NH4];
       auto read_stage = [&](int st, int buf) {
 #pragma unroll
         for (int j = 0; j < STG; ++j) {
-          const int i = st * STG + j;
-          kvb[buf][j] = *reinterpret_cast<const u32x4*>(&kt[lane][i * 8]);
+          const int c0 = (D / 2) * chh + 8 * (st * STG + j);
+          kvb[buf][j] = *reinterpret_cast<const u32x4*>(&kt[tl][c0]);
 #pragma unroll
           for (int n = 0; n < NH4; ++n) {
-            qab[buf][j][n] = *reinterpret_cast<const u32x4*>(&qT[gt][4 * n + (lane & 3)][8 * i]);
-            qbb[buf][j][n] = *reinterpret_cast<const u32x4*>(&qL[gt][4 * n + (lane & 3)][8 * i]);
+            qab[buf][j][n] = *reinterpret_cast<const u32x4*>(&qT[4 * n + (lane & 3)][c0]);
+            qbb[buf][j][n] = *reinterpret_cast<const u32x4*>(&qL[4 * n + (lane & 3)][c0]);
           }
         }
       };
@@ -350,9 +361,9 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
           read_stage(st + 1, (st + 1) & 1);
         } else {
 #pragma unroll
-          for (int i = 0; i < 64 / 8; ++i)
+          for (int i = 0; i < NPIECE; ++i)
 #pragma unroll
-            for (int n = 0; n < NH4; ++n) zab[i][n] = *reinterpret_cast<const u32x4*>(&aT[gt][4 * n + (lane & 3)][8 * i]);
+            for (int n = 0; n < NH4; ++n) zab[i][n] = *reinterpret_cast<const u32x4*>(&aT[4 * n + (lane & 3)][32 * chh + 8 * i]);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -377,7 +388,7 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int i = 0; i < 64 / 8; ++i) {
+      for (int i = 0; i < NPIECE; ++i) {
 #pragma unroll
         for (int n = 0; n < NH4; ++n) {
           const u32x4 za = zab[i][n];
@@ -386,10 +397,15 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
         }
       }
 #pragma unroll
-      for (int h = 0; h < NH; ++h)
-        s[h] = __builtin_fmaf(su[h / 4][h % 4] + sl[h / 4][h % 4], ftok, (sm[h / 4][h % 4] + sn2[h / 4][h % 4]) + sz[h / 4][h % 4]) *
-               (c_log2 * pow2f(qe[h] - shk));
+      for (int h = 0; h < NH; ++h) {
+        float part = __builtin_fmaf(su[h / 4][h % 4] + sl[h / 4][h % 4], ftok, (sm[h / 4][h % 4] + sn2[h / 4][h % 4]) + sz[h / 4][h % 4]);
+        part += __shfl_xor(part, SUB);                    // the other half of the channels
+        part *= c_log2 * pow2f(qe[h] - shk);
+        s[h] = (sp == 0 || chh == sp) ? part : s[h];      // lane = token from here on: 32 sp + (lane % 32)
+      }
     }
+    __syncthreads();                                      // the score pass has left the tile
+
     // ---- stage this lane's packed value row (in the key tile's memory, which the score pass has left),
     // and ask for the rows the value pass will want: used after the softmax
 #pragma unroll
