@@ -146,12 +146,15 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
   // wavefront, whose LDS operations complete in order).  14 to 20 KB per workgroup with the window
   // pass's arrays: eight workgroups to a compute unit, two wavefronts to a SIMD.
   constexpr int SUB = 32;                              // tokens per key sub-pass
-  constexpr int kTablesHalves = (NG + 1) * 4 * NH * 16 + NG * 64;
+  // rows of 16 tokens in the weight tables, 20 halves apart: the 16 rows that one 64-bit read touches
+  // (four token classes x four heads) then start in 16 different pairs of banks
+  constexpr int PROW = 20;
+  constexpr int kTablesHalves = (NG + 1) * 4 * NH * PROW + NG * 4 * PROW;
   constexpr int kKeyBytes = SUB * KROW * 2, kValueBytes = kTablesHalves * 2 + TILE * (ROWW + 1) * 4;
   __shared__ __attribute__((aligned(16))) unsigned char region[kKeyBytes > kValueBytes ? kKeyBytes : kValueBytes];
   _Float16 (*kt)[KROW] = reinterpret_cast<_Float16 (*)[KROW]>(region);
-  _Float16 (*pT)[4 * NH * 16] = reinterpret_cast<_Float16 (*)[4 * NH * 16]>(region);           // [NG + 1][token % 4][head][token / 4]
-  _Float16 (*zT)[4 * 16] = reinterpret_cast<_Float16 (*)[4 * 16]>(region + (NG + 1) * 4 * NH * 16 * 2);   // [NG][token % 4][token / 4]
+  _Float16 (*pT)[4 * NH * PROW] = reinterpret_cast<_Float16 (*)[4 * NH * PROW]>(region);       // [NG + 1][token % 4][head][token / 4]
+  _Float16 (*zT)[4 * PROW] = reinterpret_cast<_Float16 (*)[4 * PROW]>(region + (NG + 1) * 4 * NH * PROW * 2);   // [NG][token % 4][token / 4]
   uint32_t (*vcode)[ROWW + 1] = reinterpret_cast<uint32_t (*)[ROWW + 1]>(region + kTablesHalves * 2);     // packed value rows (padded)
 
   // ---- query: this lane's two channels of every head, each head scaled by a power of two into [1/4, 1/2)
@@ -462,7 +465,7 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
           vzn[gp] = vsn[gp] * half2_t{(_Float16)(-kLevel), (_Float16)(-kLevel)};
         }
       }
-      const int slot = (lane & 3) * 16 + (lane >> 2);
+      const int slot = (lane & 3) * PROW + (lane >> 2);
 #pragma unroll
       for (int gp = 0; gp < (NG + 1) / 2; ++gp)        // Zeff + kMid S (see kMid)
         vzn[gp] = __builtin_elementwise_fma(vsn[gp], half2_t{(_Float16)kMid, (_Float16)kMid}, vzn[gp]);
@@ -471,7 +474,7 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
 #pragma unroll
       for (int h = 0; h < NH; ++h) {
         const _Float16 p16 = (_Float16)__builtin_amdgcn_exp2f(s[h] - m_run[h]);
-        const int idx = ((lane & 3) * NH + h) * 16 + (lane >> 2);
+        const int idx = ((lane & 3) * NH + h) * PROW + (lane >> 2);
         pT[NG][idx] = p16;
 #pragma unroll
         for (int g = 0; g < NG; ++g) pT[g][idx] = p16 * vsn[g / 2][g & 1];
@@ -485,10 +488,10 @@ attention_outer_kernel(AttnArgs a, int n_both, int n_splits, WindowSet win) {
     auto read_weights = [&](int kq) {
 #pragma unroll
       for (int n = 0; n < NH4; ++n) {
-        aops[kq][n] = *reinterpret_cast<const half4_t*>(&pT[gch][(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
-        aopls[kq][n] = *reinterpret_cast<const half4_t*>(&pT[NG][(tg * NH + 4 * n + (lane & 3)) * 16 + 4 * kq]);
+        aops[kq][n] = *reinterpret_cast<const half4_t*>(&pT[gch][(tg * NH + 4 * n + (lane & 3)) * PROW + 4 * kq]);
+        aopls[kq][n] = *reinterpret_cast<const half4_t*>(&pT[NG][(tg * NH + 4 * n + (lane & 3)) * PROW + 4 * kq]);
       }
-      zops[kq] = *reinterpret_cast<const half4_t*>(&zT[gch][tg * 16 + 4 * kq]);
+      zops[kq] = *reinterpret_cast<const half4_t*>(&zT[gch][tg * PROW + 4 * kq]);
     };
     if constexpr (kAhead) {
 #pragma unroll
