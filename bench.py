@@ -228,9 +228,9 @@ def compare_kinds(torch, iq, hip, w, cfg, args, gen, inner_kernel_ms, stream):
         n_inst = 3 if kind_name == "outer" else 2
         caches = [make_instance(torch, iq, w, c2, i, w.n_tokens, gen) for i in range(n_inst)]
         ws = iq.allocate_workspace(c2)
-        n = 12 if kind_name == "fp16" else 24
+        n = 24 if kind_name == "fp16" else 48
         evs = [(hip.event(), hip.event()) for _ in range(n)]
-        for i in range(6):
+        for i in range(n):                               # (as many untimed calls as timed ones)
             iq.innerq_decode_attention(caches[i % n_inst], q, ws, out=o, stream=stream)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
