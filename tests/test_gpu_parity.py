@@ -166,21 +166,57 @@ def test_attention_keys_near_the_top_of_fp16(env, bits, mode):
     assert max_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
 @pytest.mark.parametrize("log2_q", [-13, -6, 6])
 @pytest.mark.parametrize("bits,mode", [(2, orc.SYM), (2, orc.HYBRID), (3, orc.HYBRID), (4, orc.HYBRID)])
-def test_attention_query_magnitudes(env, bits, mode, log2_q):
+def test_attention_query_magnitudes(env, bits, mode, log2_q, kind):
     """Queries scaled by 2^-13 (mostly fp16 denormals), 2^-6 and 2^6, keys scaled the other way so
-    that the scores keep their size: the fused kernel's query table carries a power of two per
-    head, so its accuracy must not depend on the magnitude of q."""
+    that the scores keep their size: the fused kernels' query tables carry a power of two per
+    head (the outer-grouped one a second one per tile for the scales folded in), so their accuracy
+    must not depend on the magnitude of q or of the keys."""
     torch, iq = env
     w = small(bits=bits, k_mode=mode, v_mode=mode, n_tokens=900)
-    o = oracle_config(w)
+    o = oracle_config(w, kind=kind)
     K, V = wl.kv_full(w)
     K = np.clip(K.astype(np.float32) * 2.0 ** (-log2_q - 1), -6.0e4, 6.0e4).astype(np.float16)
     q = (wl.query(w).astype(np.float32) * 2.0 ** log2_q).astype(np.float16)
     want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
     _, got = run_attention(torch, iq, o, K, V, q)
     assert max_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
+@pytest.mark.parametrize("order", ["rising", "falling"])
+@pytest.mark.parametrize("bits,mode", [(2, orc.SYM), (2, orc.HYBRID), (4, orc.HYBRID)])
+def test_attention_value_magnitudes_change_along_the_context(env, bits, mode, order, kind):
+    """Values whose magnitude changes by 2^10 from one third of the context to the next, in both
+    directions: the outer-grouped kernel folds the tokens' value scales into the softmax weights under
+    a running power of two that has to follow the largest scale seen so far (and must not lose the
+    small tokens while they are all there is); the other kernels must not care."""
+    torch, iq = env
+    w = small(bits=bits, k_mode=mode, v_mode=mode, n_tokens=1100)
+    o = oracle_config(w, kind=kind)
+    K, V = wl.kv_full(w)
+    third = w.n_tokens // 3
+    steps = [-10, 0, 10] if order == "rising" else [10, 0, -10]
+    V = V.astype(np.float32)
+    for i, e in enumerate(steps):
+        V[:, :, i * third:(i + 1) * third if i < 2 else w.n_tokens] *= 2.0 ** e
+    V = np.clip(V, -6.0e4, 6.0e4).astype(np.float16)
+    q = wl.query(w)
+    want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
+    _, got = run_attention(torch, iq, o, K, V, q)
+    assert np.isfinite(got).all()
+    assert max_rel_err(got, want) <= TOL
+    # the small third on its own (a cache that never sees a large scale)
+    n_small = third if order == "rising" else w.n_tokens - 2 * third
+    sl = slice(0, third) if order == "rising" else slice(2 * third, w.n_tokens)
+    w2 = small(bits=bits, k_mode=mode, v_mode=mode, n_tokens=n_small)
+    o2 = oracle_config(w2, kind=kind)
+    K2, V2 = np.ascontiguousarray(K[:, :, sl]), np.ascontiguousarray(V[:, :, sl])
+    want2 = orc.decode_attention(o2, orc.cache_init_prefill(o2, K2, V2), q)
+    _, got2 = run_attention(torch, iq, o2, K2, V2, q)
+    assert max_rel_err(got2, want2) <= TOL
 
 
 @pytest.mark.parametrize("n_tokens", [1, 2, 4, 5, 51, 52, 53, 83, 84, 85, 116, 117, 180])
@@ -198,12 +234,13 @@ def test_attention_edge_lengths(env, kind, n_tokens):
     assert max_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
 @pytest.mark.parametrize("heads", [(4, 4), (2, 1), (16, 2), (12, 4)])
-def test_attention_head_ratios(env, heads):
+def test_attention_head_ratios(env, heads, kind):
     torch, iq = env
     hq, hk = heads
     w = small(n_q_heads=hq, n_kv_heads=hk, n_tokens=600)
-    o = oracle_config(w)
+    o = oracle_config(w, kind=kind)
     K, V = wl.kv_full(w)
     q = wl.query(w)
     want = orc.decode_attention(o, orc.cache_init_prefill(o, K, V), q)
