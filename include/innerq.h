@@ -243,8 +243,11 @@ int innerq_prefill(const innerq_config_t *cfg, innerq_cache_t *cache, const void
  * kernels the query (after q_scale) enters the matrix cores as fp16 times a power of two.  The
  * inner-grouped kernel chooses that power per head from the head's largest |q|, so every finite
  * fp16 query is accepted and the accuracy does not depend on its magnitude.  The outer-grouped
- * comparison kernel multiplies the fp16 query as it is with keys dequantised to fp16: there the
- * dequantised keys must stay within the fp16 range (nothing checks this: device data). */
+ * comparison kernel folds the groups' scales into the query (keys) and into the softmax weights
+ * (values) as fp16 tables; it normalises the query per head and the scales and zero-points per
+ * 64-token tile by powers of two, so the magnitudes of query and cache do not matter either, as
+ * long as the scales and zero-points of one tile lie within 2^14 of each other (smaller ones
+ * lose precision against the tile's largest, not against themselves). */
 int innerq_decode_attention(const innerq_config_t *cfg, const innerq_cache_t *cache,
                             const void *q_fp16, const float *q_scale, void *out, int out_is_fp32,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
