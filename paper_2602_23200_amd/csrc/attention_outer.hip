@@ -37,11 +37,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = kHeadDim;
 constexpr int TILE = 64;
-constexpr int KROW = D + 8;                 // padded LDS row of the dequantised key tile (halves)
+constexpr int KROW = D + 8;                 // padded LDS row of the token-major key tile (halves)
 
-// wave-wide reductions: the DPP forms shared with the window pass
+// wave-wide maximum: the DPP form shared with the window pass
 __device__ inline float wave_max_o(float x) { return window_wave_max(x); }
-__device__ inline float wave_sum_o(float x) { return window_wave_sum(x); }
 __device__ inline float half_lo(uint32_t p) { return __half2float(__ushort_as_half((unsigned short)(p & 0xffffu))); }
 __device__ inline float half_hi(uint32_t p) { return __half2float(__ushort_as_half((unsigned short)(p >> 16))); }
 
