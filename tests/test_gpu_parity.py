@@ -552,14 +552,16 @@ def _random_case(i):
                 v_mode=modes[int(r.integers(3))], seed=500 + i), v_bits
 
 
+@pytest.mark.parametrize("kind", [orc.KIND_INNER, orc.KIND_OUTER])
 @pytest.mark.parametrize("i", range(24))
-def test_random_configurations(env, i):
+def test_random_configurations(env, i, kind):
     """Seeded random shapes, widths, modes, windows and lengths (ragged tiles, windows longer than
-    the context, 1 to 8 query heads per kv head): cache bit-exact, attention within tolerance."""
+    the context, 1 to 8 query heads per kv head), for both groupings: cache bit-exact, attention
+    within tolerance."""
     torch, iq = env
     kw, v_bits = _random_case(i)
     w = small(**kw)
-    o = oracle_config(w, v_bits=v_bits)
+    o = oracle_config(w, kind=kind, v_bits=v_bits)
     K, V = wl.kv_full(w)
     q = wl.query(w)
     want_cache = orc.cache_init_prefill(o, K, V)
