@@ -632,6 +632,12 @@ def main():
                    "layers": n_layers, "cache_instances": n_inst},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
+                     # the recorded HBM bytes (fetched + written, everything the launch moves: the quantised
+                     # range, the fp16 windows, the queries, the split-K partials) over this run's kernel time:
+                     # the rate the memory system actually sustains, next to the algorithmic one above
+                     **({"traffic_GBps": traffic / (kern_ms * 1e-3) / 1e9,
+                         "traffic_frac_of_peak": traffic / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic_bytes_per_token_kvhead": traffic / units} if traffic else {}),
                      "kernel": "fused dequant score+value pass over the quantised range",
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_ms_median,
                      "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_token_kvhead": per_unit,
